@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE expert layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral_T4096]
+
+One "step" is one moe_layer_forward call (router, dispatch, both expert GEMMs, combine) over one
+batch of seeded synthetic tokens already resident in HBM.  Prints one JSON line: whole-layer
+useful TFLOP/s, ms per step, the roofline figures of the dominant kernel (GEMM1 + SwiGLU), and the
+CPU oracle timed on a bounded sample of the same workload on this machine's host cores.
+
+`--curve` additionally sweeps the skewed Mixtral-shaped workload over token loads and writes the
+latency-vs-token-load table (the per-GPU profile the paper's mapping search consumes, Sec. 3.3.2)
+to gpurun_out/latency_curve.json.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (published)
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def make_workload(name, seed, weights):
+    import workloads as wl
+    if name.startswith("mixtral_skewed_T"):
+        return wl.mixtral_skewed(int(name.split("T")[-1]), seed, weights=weights)
+    if name.startswith("mixtral_T"):
+        return wl.mixtral(int(name.split("T")[-1]), seed, weights=weights)
+    if name.startswith("fine_grained_T"):
+        return wl.fine_grained(int(name.split("T")[-1]), seed, weights=weights)
+    if name.startswith("ep_share_T"):
+        return wl.ep_share_layer(int(name.split("T")[-1]), seed, weights=weights)
+    if name == "tiny":
+        return wl.tiny(seed)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def time_layer(ctx, x, rp, bias, packed, out, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        ctx.moe_layer_forward(x, rp, bias, packed, out=out)
+    torch.cuda.synchronize()
+    try:
+        ctx.moe_stage_times()          # drop earlier calls from the stage averages
+    except Exception:
+        pass
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        ctx.moe_layer_forward(x, rp, bias, packed, out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt / steps * 1e3, ctx.moe_stage_times()
+
+
+def cpu_baseline(inp, sample_tokens):
+    """The oracle as it stands, on a bounded sample of the workload's tokens, on the host cores."""
+    import numpy as np
+    from oracle import moe_oracle as orc          # bench's cpu_baseline leg may use the oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    s = inp.shape
+    n = min(sample_tokens, s.T)
+    tokens = np.linspace(0, s.T - 1, n).astype(np.int64)
+    t0 = time.perf_counter()
+    r = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k, e_lo=s.e_lo, tokens=tokens)
+    dt = time.perf_counter() - t0
+    local = ((r["idx"][tokens] >= s.e_lo) & (r["idx"][tokens] < s.e_lo + s.E_local)).sum()
+    flops = 6.0 * local * s.d * s.f + 2.0 * s.T * s.d * s.E
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n} of {s.T} tokens ({int(local)} expert rows) of the same workload, fp64 numpy, "
+                      f"{dt:.1f} s wall"}
+
+
+def run_curve(moe, gu, weights_dev_packed, args):
+    """Latency vs per-GPU token load on the skewed Mixtral-shaped workload."""
+    import torch
+    import workloads as wl
+    ctx_shape = (wl.MIXTRAL_D, wl.MIXTRAL_F, wl.MIXTRAL_E, wl.MIXTRAL_K)
+    loads = [int(v) for v in args.curve_loads.split(",")]
+    rows = []
+    ctx = moe.MoEContext(max(loads), *ctx_shape, flags=moe.FLAG_STAGE_EVENTS)
+    for T in loads:
+        inp = wl.mixtral_skewed(T, args.seed, weights=False)
+        x = gu.to_dev_bf16(inp.x)
+        rp = ctx.moe_pack_router(gu.to_dev(inp.Wg))
+        bias = gu.to_dev(inp.bias)
+        out = torch.empty(T, wl.MIXTRAL_D, dtype=torch.bfloat16, device="cuda")
+        counts = torch.empty(wl.MIXTRAL_E, dtype=torch.int32, device="cuda")
+        ctx.moe_layer_forward(x, rp, bias, weights_dev_packed, out=out, counts_out=counts)
+        ms, stages = time_layer(ctx, x, rp, bias, weights_dev_packed, out, args.curve_steps, 3)
+        flops = 6.0 * T * wl.MIXTRAL_K * wl.MIXTRAL_D * wl.MIXTRAL_F + 2.0 * T * wl.MIXTRAL_D * wl.MIXTRAL_E
+        rows.append({"tokens": T, "ms": ms, "tflops": flops / ms / 1e9, "tile_rows": ctx.moe_tile_rows(),
+                     "expert_counts": counts.cpu().tolist(), "stages_ms": stages})
+        log(f"curve T={T}: {ms:.3f} ms  {flops / ms / 1e9:.1f} TFLOP/s  counts={counts.cpu().tolist()}")
+    ctx.close()
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "latency_curve.json"), "w") as fh:
+        json.dump({"workload": "mixtral_skewed", "rows": rows}, fh, indent=1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mixtral_T4096")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--tile-class", type=int, default=-1)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--curve", action="store_true")
+    ap.add_argument("--curve-loads", default="512,1024,2048,4096,8192")
+    ap.add_argument("--curve-steps", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU's expert layer: this build has no multi-GPU path; "
+                         "run with --gpus 1")
+    if args.steps > 64:
+        raise SystemExit("--steps is limited to 64 (the per-stage event ring holds 64 calls)")
+
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (the HIP path has no CPU fallback)")
+    import paper_2605_19945_amd as moe
+    import gpu_util as gu
+    moe.load_library()
+
+    t0 = time.perf_counter()
+    inp = make_workload(args.workload, args.seed, None)
+    s = inp.shape
+    log(f"workload {inp.name}: T={s.T} d={s.d} f={s.f} E={s.E} k={s.k} local=[{s.e_lo},{s.e_lo + s.E_local}) "
+        f"generated in {time.perf_counter() - t0:.1f} s")
+
+    ctx = moe.MoEContext(s.T, s.d, s.f, s.E, s.k, s.e_lo, s.E_local, flags=moe.FLAG_STAGE_EVENTS)
+    ctx.moe_set_tile_class(args.tile_class)
+    x = gu.to_dev_bf16(inp.x)
+    rp = ctx.moe_pack_router(gu.to_dev(inp.Wg))
+    bias = gu.to_dev(inp.bias) if inp.bias is not None else None
+    W1, W3, W2 = gu.to_dev_bf16(inp.W1), gu.to_dev_bf16(inp.W3), gu.to_dev_bf16(inp.W2)
+    packed = ctx.moe_pack_weights(W1, W3, W2)
+    torch.cuda.synchronize()
+    del W1, W3, W2
+    torch.cuda.empty_cache()
+    out = torch.empty(s.T, s.d, dtype=torch.bfloat16, device="cuda")
+    counts = torch.empty(s.E, dtype=torch.int32, device="cuda")
+    ctx.moe_layer_forward(x, rp, bias, packed, out=out, counts_out=counts)
+    torch.cuda.synchronize()
+    cnt = counts.cpu().numpy()
+    A_local = int(cnt[s.e_lo:s.e_lo + s.E_local].sum())
+
+    ms, stages = time_layer(ctx, x, rp, bias, packed, out, args.steps, args.warmup)
+    flops_ffn = 6.0 * A_local * s.d * s.f
+    flops = flops_ffn + 2.0 * s.T * s.d * s.E
+    tflops = flops / ms / 1e9
+    g1 = 4.0 * A_local * s.d * s.f / stages["gemm1"] / 1e9
+    g2 = 2.0 * A_local * s.d * s.f / stages["gemm2"] / 1e9
+    route_gbs = (s.T * s.d * 2 + s.T * s.k * 8) / stages["route"] / 1e6
+    combine_gbs = ((A_local + s.T) * s.d * 2 + A_local * 8) / stages["combine"] / 1e6
+    log(f"layer {ms:.3f} ms/step -> {tflops:.1f} TFLOP/s; stages (ms): "
+        + ", ".join(f"{k}={v:.4f}" for k, v in stages.items()))
+    log(f"gemm1 {g1:.1f} TFLOP/s ({g1 / PEAK_BF16_TFLOPS:.1%} of bf16 peak), gemm2 {g2:.1f} TFLOP/s "
+        f"({g2 / PEAK_BF16_TFLOPS:.1%}); route {route_gbs:.0f} GB/s, combine {combine_gbs:.0f} GB/s "
+        f"(stage intervals include launch gaps); tile rows {ctx.moe_tile_rows()}; counts {cnt.tolist()}")
+
+    result = {
+        "metric": "MoE layer TFLOP/s + latency vs per-GPU token load (Mixtral-8x7B shape, 1 GPU)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": inp.name, "T": s.T, "d": s.d, "f": s.f, "E": s.E, "k": s.k,
+                   "E_local": s.E_local, "local_assignments": A_local, "tile_rows": ctx.moe_tile_rows(),
+                   "stages_ms": stages},
+        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel<SwiGLU> (GEMM1)", "achieved": g1,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": g1 / PEAK_BF16_TFLOPS,
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_tokens)
+    if args.curve:
+        run_curve(moe, gu, packed, args)
+    ctx.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

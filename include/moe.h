@@ -1,0 +1,164 @@
+/* moe.h -- C ABI of the per-GPU Mixture-of-Experts expert layer for AMD MI355X (gfx950).
+ *
+ * The layer is the one GEM (GPU-variability-aware expert-to-GPU mapping) profiles and balances:
+ * a router selects the top-k of E experts for every token (paper Sec. 2.1), the token is sent to
+ * the GPU holding those experts, each expert is a feed-forward network, and the results return
+ * to the token (Sec. 7).  The latency of this layer as a function of the number of tokens a GPU
+ * receives is the per-GPU curve C_g(n) of the paper's score (Sec. 3.3.3, Eq. 1); the per-expert
+ * token counts are one row of its expert-utilisation trace (Sec. 3.3.1).  The paper gives no
+ * formulas for the layer itself; the ones used here are the standard ones: softmax over the k
+ * selected router logits, SwiGLU experts  y = W2^T( silu(W1^T x) * (W3^T x) ).
+ *
+ * Conventions
+ *   - Every tensor pointer is DEVICE memory owned by the caller, unless marked "host".
+ *     The library allocates no device memory: its scratch is the workspace given to moe_create.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls enqueue
+ *     work on it and return; none synchronises with the host.
+ *   - bf16 tensors are passed as void*; they are row-major and 16-byte aligned.
+ *   - Shapes: T tokens, d model width, f expert width, E experts seen by the router, k experts
+ *     per token, experts [e_lo, e_lo+E_local) resident on this GPU.  d and f must be multiples
+ *     of 64; 1 <= k <= min(E, 16); E <= 256; 1 <= E_local <= E.
+ *   - Errors are return codes.  Arguments are validated on the host before any launch; a call
+ *     that returns an error has launched nothing.  T == 0 is MOE_OK and a no-op.
+ *   - Calls on one moe_ctx must not overlap in time (they share its workspace).
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ctx moe_ctx; /* opaque, host memory */
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = 1,        /* null / misaligned pointer, T out of range, ...          */
+    MOE_ERR_UNSUPPORTED_SHAPE = 2,  /* shape outside the limits listed above                   */
+    MOE_ERR_WORKSPACE_TOO_SMALL = 3,
+    MOE_ERR_DEVICE = 4              /* a HIP call failed (launch error, wrong architecture)    */
+} moe_status;
+
+typedef struct {
+    int32_t T_max;    /* largest T any call will pass                                          */
+    int32_t d, f;     /* model width, expert FFN width                                         */
+    int32_t E, k;     /* experts seen by the router, experts per token                         */
+    int32_t e_lo;     /* first resident expert                                                 */
+    int32_t E_local;  /* number of resident experts (== E: all of them)                        */
+    uint32_t flags;   /* MOE_FLAG_*                                                            */
+} moe_shape;
+
+#define MOE_FLAG_STAGE_EVENTS 1u /* moe_layer_forward records HIP events around every stage   */
+
+enum { MOE_STAGE_ROUTE = 0, MOE_STAGE_PERMUTE = 1, MOE_STAGE_GEMM1 = 2, MOE_STAGE_GEMM2 = 3,
+       MOE_STAGE_COMBINE = 4, MOE_NUM_STAGES = 5 };
+
+const char* moe_status_string(moe_status s);
+
+/* Text of the most recent failing HIP call behind a MOE_ERR_DEVICE on this thread ("" if none).
+ * The pointer stays valid; the text changes with the next device error. */
+const char* moe_last_device_error(void);
+
+/* Bytes of device workspace a context of this shape needs (0 if the shape is unsupported). */
+size_t moe_workspace_bytes(const moe_shape* shape /* host */);
+
+/* Creates a context over a caller-owned device workspace of at least moe_workspace_bytes().
+ * The workspace must stay valid until moe_destroy.  Must be called with the target device
+ * current.  *ctx is NULL on error. */
+moe_status moe_create(moe_ctx** ctx, const moe_shape* shape /* host */, void* workspace,
+                      size_t workspace_bytes);
+void moe_destroy(moe_ctx* ctx);
+
+/* Number of rows the staged buffers (xp, y, tok_of) must hold for T tokens:
+ * T * min(k, E_local), the largest possible number of local (token, expert) assignments. */
+int64_t moe_rows_capacity(const moe_shape* shape /* host */, int32_t T);
+
+/* ---- one-off, at model-load time (the analogue of loading each expert's weights onto its
+ * assigned GPU, paper Sec. 3.3.4); not part of the layer latency ------------------------------ */
+
+/* Router matrix Wg [d, E] fp32 row-major -> opaque packed form (two bf16 terms per weight,
+ * transposed so the reduction dimension is contiguous). */
+size_t moe_packed_router_bytes(const moe_shape* shape /* host */);
+moe_status moe_pack_router(moe_ctx* ctx, const float* Wg, void* router_packed, void* stream);
+
+/* Expert weights W1, W3 [E_local, d, f] and W2 [E_local, f, d], bf16 row-major -> opaque packed
+ * form (transposed so the reduction dimension is contiguous; W1 and W3 interleaved in blocks of
+ * 32 output columns so one accumulator tile holds both branches of the SwiGLU). */
+size_t moe_packed_weight_bytes(const moe_shape* shape /* host */);
+moe_status moe_pack_weights(moe_ctx* ctx, const void* W1, const void* W3, const void* W2,
+                            void* packed, void* stream);
+
+/* ---- the hot path ---------------------------------------------------------------------------- */
+
+/* Router (paper Sec. 2.1 "a router selects a subset of experts for each token"; Sec. 3.3.1):
+ *   logit[t,e] = sum_i x[t,i] * Wg[i,e] (+ bias[e]);  topk_idx[t,0..k) = the k largest, slot 0
+ *   the largest, equal logits resolved to the lower expert index;  topk_w[t,j] = softmax over
+ *   the k selected logits;  counts[e] = number of (t, j) with topk_idx[t,j] == e, over all E.
+ * x [T, d] bf16; bias [E] fp32 or NULL; topk_idx [T, k] int32; topk_w [T, k] fp32;
+ * counts [E] int32 (overwritten). */
+moe_status moe_route(moe_ctx* ctx, const void* x, const void* router_packed, const float* bias,
+                     int32_t T, int32_t* topk_idx, float* topk_w, int32_t* counts, void* stream);
+
+/* Dispatch by expert (paper Sec. 2.1 "dispatches it to the GPU(s) hosting those experts"):
+ *   offsets[e'] = number of assignments to resident experts before e_lo + e' (exclusive prefix
+ *   sum, offsets[E_local] = number of local assignments);  the destination row of (t, j) with
+ *   e = topk_idx[t,j] resident is row_of[t,j] = offsets[e-e_lo] + #{t' < t : t' selected e}
+ *   (expert-contiguous, ascending token order inside an expert); row_of = -1 for non-resident
+ *   experts;  tok_of[row] = t;  xp[row, :] = x[t, :].
+ * xp [rows_capacity, d] bf16 or NULL (skip the row copy); offsets [E_local+1]; row_of [T, k];
+ * tok_of [rows_capacity]. */
+moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T, void* xp,
+                       int32_t* offsets, int32_t* row_of, int32_t* tok_of, void* stream);
+
+/* Expert FFN over expert-contiguous rows (the paper's "isolated MoE expert kernel", Sec. 3.3.2):
+ *   for offsets[e'] <= r < offsets[e'+1]:
+ *       y[r, :] = W2[e']^T ( silu(W1[e']^T xp[r]) * (W3[e']^T xp[r]) )
+ *   bf16 operands, fp32 accumulation; the intermediate [rows, f] is stored as bf16 in the
+ *   workspace.  Experts with no rows cost nothing and their weights are not read.
+ * xp, y [n_rows_cap, d] bf16; offsets [E_local+1] (device; values are not read by the host);
+ * n_rows_cap: host upper bound on offsets[E_local], at most moe_rows_capacity(shape, T_max). */
+moe_status moe_grouped_ffn(moe_ctx* ctx, const void* xp, const int32_t* offsets,
+                           int32_t n_rows_cap, const void* packed, void* y, void* stream);
+
+/* Weighted return to token order (paper Sec. 7: tokens return to their origin):
+ *   out[t, :] = sum_j topk_w[t,j] * y[row_of[t,j], :]   (slots with row_of < 0 contribute 0),
+ *   summed in slot order in fp32, one write per output element, no atomics.
+ * y [rows_capacity, d] bf16; out [T, d] bf16. */
+moe_status moe_combine(moe_ctx* ctx, const void* y, const int32_t* row_of, const float* topk_w,
+                       int32_t T, void* out, void* stream);
+
+/* The whole layer on one stream with no host synchronisation: route, dispatch, experts, combine.
+ * Intermediates live in the workspace; the row copy is folded into the first GEMM's operand load.
+ * With E_local < E, `out` is this GPU's partial sum (tokens with no resident expert give 0).
+ * counts_out [E] int32 or NULL. */
+moe_status moe_layer_forward(moe_ctx* ctx, const void* x, const void* router_packed,
+                             const float* bias, const void* packed, int32_t T, void* out,
+                             int32_t* counts_out, void* stream);
+
+/* ---- introspection --------------------------------------------------------------------------- */
+
+/* Mean milliseconds of each stage over the moe_layer_forward calls made since the previous
+ * read-out (at most the 64 most recent) on a context created with MOE_FLAG_STAGE_EVENTS.
+ * Blocks until the last of those calls has completed.  ms: host, MOE_NUM_STAGES floats. */
+moe_status moe_stage_times(moe_ctx* ctx, float* ms /* host */);
+
+/* Token-tile height of the expert GEMMs for this shape: per-expert row counts are rounded up to
+ * a multiple of it, which sets the staircase of the latency-vs-load curve (paper Sec. 3.3.2). */
+int32_t moe_tile_rows(const moe_ctx* ctx);
+
+/* Tuning hook: force the token-tile class of the expert GEMMs (0: 32 rows, 1: 64, 2: 128, 3: 256;
+ * -1: choose from the expected rows per expert, the default). */
+moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
+
+/* Device pointers into the workspace holding the intermediates of the most recent
+ * moe_layer_forward: topk_idx [T,k], topk_w [T,k], offsets [E_local+1], row_of [T,k]. */
+moe_status moe_layer_intermediates(moe_ctx* ctx, const int32_t** topk_idx, const float** topk_w,
+                                   const int32_t** offsets, const int32_t** row_of);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

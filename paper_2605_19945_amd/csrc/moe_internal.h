@@ -1,0 +1,89 @@
+// Internal declarations shared by the translation units of libmoe (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moe.h"
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// One work item of a grouped GEMM launch: BM rows of one expert times BN packed weight rows.
+struct TileDesc {
+    int32_t expert;  // local expert index
+    int32_t row0;    // first row (in the expert-contiguous row space)
+    int32_t rows;    // valid rows in this tile (0: nothing to do)
+    int32_t n0;      // first packed weight row
+};
+
+// Token-tile classes of the grouped GEMM.
+enum GemmClass { GEMM_BM32 = 0, GEMM_BM64 = 1, GEMM_BM128 = 2, GEMM_BM256 = 3, GEMM_NUM_CLASSES };
+
+struct GemmPlan {
+    int cls;         // GemmClass
+    int bm, bn;      // tile: bm rows x bn packed weight rows
+    int mt_max;      // upper bound on the number of row tiles
+    int nt1, nt2;    // weight-row tiles of GEMM1 (2f packed rows) and GEMM2 (d rows)
+    int grid1, grid2;
+};
+
+constexpr int MOE_EVENT_RING = 64;
+
+struct moe_ctx {
+    moe_shape s;
+    int device;
+    char* ws;
+    size_t ws_bytes;
+    // workspace carve-up (device pointers)
+    int32_t* idx;        // [T_max, k]
+    float* w;            // [T_max, k]
+    int32_t* counts;     // [E]
+    int32_t* offsets;    // [E_local + 1]
+    int32_t* row_of;     // [T_max, k]
+    int32_t* tok_of;     // [rows_cap]
+    int32_t* blockhist;  // [nblk_max, E_local]
+    TileDesc* table1;    // [grid1_max]
+    TileDesc* table2;    // [grid2_max]
+    uint16_t* H;         // [rows_cap, f] bf16
+    uint16_t* Y;         // [rows_cap, d] bf16
+    int64_t rows_cap;
+    int table1_cap, table2_cap;
+    hipEvent_t (*ev)[MOE_NUM_STAGES + 1];  // ring of MOE_EVENT_RING event sets, or nullptr
+    int ev_count;                          // layer calls recorded since the last read-out
+    int last_cls;    // tile class of the most recent expert GEMM launch
+    int forced_cls;  // -1: pick by expected rows per expert
+};
+
+static inline int64_t moe_round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+static inline int moe_router_rows(int E) {  // packed router rows: multiple of 16, power-of-two blocks
+    int nb = (E + 15) / 16;
+    int p = 1;
+    while (p < nb) p *= 2;
+    return p * 16;
+}
+
+// ---- launchers (each validates nothing; the C-ABI layer has done that) -------------------------
+hipError_t launch_pack_router(const float* Wg, int d, int E, uint16_t* rp, hipStream_t st);
+hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uint16_t* W2, int E_local,
+                               int d, int f, uint16_t* packed, hipStream_t st);
+hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias, int T, int d, int E,
+                        int k, int32_t* idx, float* w, int32_t* counts, hipStream_t st);
+hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
+                          int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st);
+hipError_t launch_gather(const uint16_t* x, const int32_t* tok_of, const int32_t* offsets, int E_local,
+                         int64_t rows_cap, int d, uint16_t* xp, hipStream_t st);
+hipError_t launch_combine(const uint16_t* y, const int32_t* row_of, const float* w, int T, int k, int d,
+                          uint16_t* out, hipStream_t st);
+
+GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f);
+int gemm_pick_class(double expected_rows_per_expert);
+int gemm_class_rows(int cls);
+hipError_t gemm_init_attributes();
+hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,
+                           TileDesc* t2, hipStream_t st);
+hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
+                        const uint16_t* W13p, int d, int f, uint16_t* H, const TileDesc* table,
+                        hipStream_t st);
+hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2p, int d, int f,
+                        uint16_t* Y, const TileDesc* table, hipStream_t st);

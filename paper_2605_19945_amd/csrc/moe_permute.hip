@@ -1,0 +1,185 @@
+// Dispatch by expert: a stable counting sort of the (token, slot) assignments by resident expert.
+//
+// The paper says only that the router "dispatches [each token] to the GPU(s) hosting those
+// experts" (Sec. 2.1); inside one GPU that is the grouping of rows by expert computed here.
+// Order inside an expert is ascending token id, so the result is unique and reproducible.
+//
+// Three small kernels, no atomics on global memory, no waiting between workgroups:
+//   1. per-256-token block histogram of resident experts,
+//   2. one workgroup: exclusive scan over blocks (per expert) and over experts -> offsets,
+//   3. per block: rank of every assignment among the block's earlier tokens, from per-wavefront
+//      64-bit membership masks in LDS -> row_of, tok_of.
+// The row copy itself (xp[row] = x[tok_of[row]]) is a separate streaming kernel.
+#include "moe_internal.h"
+
+constexpr int PB = 256;  // tokens per block (one token per thread)
+constexpr int PW = PB / 64;
+
+__global__ __launch_bounds__(PB) void permute_hist_kernel(const int32_t* __restrict__ idx, int T, int k,
+                                                          int e_lo, int E_local,
+                                                          int32_t* __restrict__ blockhist) {
+    extern __shared__ int32_t hist[];  // [E_local]
+    for (int e = threadIdx.x; e < E_local; e += PB) hist[e] = 0;
+    __syncthreads();
+    int t = blockIdx.x * PB + threadIdx.x;
+    if (t < T)
+        for (int j = 0; j < k; ++j) {
+            int e = idx[(size_t)t * k + j] - e_lo;
+            if (e >= 0 && e < E_local) atomicAdd(&hist[e], 1);
+        }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E_local; e += PB) blockhist[(size_t)blockIdx.x * E_local + e] = hist[e];
+}
+
+// One workgroup of 256 threads; E_local <= 256.  blockhist[b][e] becomes the number of
+// assignments to e in blocks before b; offsets[e] the exclusive prefix over experts.
+__global__ __launch_bounds__(256) void permute_scan_kernel(int32_t* __restrict__ blockhist, int nblk,
+                                                           int E_local, int32_t* __restrict__ offsets) {
+    __shared__ int32_t tot[256];
+    int e = threadIdx.x;
+    int run = 0;
+    if (e < E_local)
+        for (int b = 0; b < nblk; ++b) {
+            int c = blockhist[(size_t)b * E_local + e];
+            blockhist[(size_t)b * E_local + e] = run;
+            run += c;
+        }
+    tot[e] = e < E_local ? run : 0;
+    __syncthreads();
+    // inclusive Hillis-Steele scan over 256 entries
+    for (int off = 1; off < 256; off <<= 1) {
+        int v = e >= off ? tot[e - off] : 0;
+        __syncthreads();
+        tot[e] += v;
+        __syncthreads();
+    }
+    if (e < E_local) offsets[e + 1] = tot[e];
+    if (e == 0) offsets[0] = 0;
+}
+
+__global__ __launch_bounds__(PB) void permute_rank_kernel(const int32_t* __restrict__ idx, int T, int k,
+                                                          int e_lo, int E_local,
+                                                          const int32_t* __restrict__ blockhist,
+                                                          const int32_t* __restrict__ offsets,
+                                                          int32_t* __restrict__ row_of,
+                                                          int32_t* __restrict__ tok_of) {
+    extern __shared__ unsigned long long masks[];  // [PW][E_local] lanes of wave w that selected e
+    int32_t* wbase = (int32_t*)(masks + PW * E_local);  // [PW][E_local] rows of e in earlier waves
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int o = tid; o < PW * E_local; o += PB) masks[o] = 0ull;
+    __syncthreads();
+    const int t = blockIdx.x * PB + tid;
+    if (t < T)
+        for (int j = 0; j < k; ++j) {
+            int e = idx[(size_t)t * k + j] - e_lo;
+            if (e >= 0 && e < E_local) atomicOr(&masks[wave * E_local + e], 1ull << lane);
+        }
+    __syncthreads();
+    for (int e = tid; e < E_local; e += PB) {
+        int run = offsets[e] + blockhist[(size_t)blockIdx.x * E_local + e];
+#pragma unroll
+        for (int ww = 0; ww < PW; ++ww) {
+            wbase[ww * E_local + e] = run;
+            run += __popcll(masks[ww * E_local + e]);
+        }
+    }
+    __syncthreads();
+    if (t < T) {
+        const unsigned long long below = (1ull << lane) - 1ull;
+        for (int j = 0; j < k; ++j) {
+            int e = idx[(size_t)t * k + j] - e_lo;
+            int r = -1;
+            if (e >= 0 && e < E_local) {
+                r = wbase[wave * E_local + e] + __popcll(masks[wave * E_local + e] & below);
+                tok_of[r] = t;
+            }
+            row_of[(size_t)t * k + j] = r;
+        }
+    }
+}
+
+hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
+                          int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st) {
+    int nblk = (T + PB - 1) / PB;
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(nblk), dim3(PB), E_local * sizeof(int32_t), st, idx, T, k,
+                       e_lo, E_local, blockhist);
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, blockhist, nblk, E_local, offsets);
+    size_t smem = (size_t)PW * E_local * (sizeof(unsigned long long) + sizeof(int32_t));
+    hipLaunchKernelGGL(permute_rank_kernel, dim3(nblk), dim3(PB), smem, st, idx, T, k, e_lo, E_local,
+                       blockhist, offsets, row_of, tok_of);
+    return hipGetLastError();
+}
+
+// xp[r, :] = x[tok_of[r], :] for r < offsets[E_local]; 16 bytes per lane, one wavefront per row
+// segment of 1 KiB, grid-stride over rows so the launch does not depend on the device-side count.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x,
+                                                          const int32_t* __restrict__ tok_of,
+                                                          const int32_t* __restrict__ offsets, int E_local,
+                                                          int chunks /* d / 8 */, uint4* __restrict__ xp) {
+    const int n_rows = offsets[E_local];
+    const int rows_per_block = blockDim.x / 64 * 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int r = blockIdx.x * rows_per_block + wave; r < n_rows; r += gridDim.x * rows_per_block) {
+        const uint4* src = x + (size_t)tok_of[r] * chunks;
+        uint4* dst = xp + (size_t)r * chunks;
+        for (int c = lane; c < chunks; c += 64) dst[c] = src[c];
+    }
+}
+
+hipError_t launch_gather(const uint16_t* x, const int32_t* tok_of, const int32_t* offsets, int E_local,
+                         int64_t rows_cap, int d, uint16_t* xp, hipStream_t st) {
+    int64_t blocks = (rows_cap + 3) / 4;
+    if (blocks > 8192) blocks = 8192;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((int)blocks), dim3(256), 0, st, (const uint4*)x, tok_of,
+                       offsets, E_local, d / 8, (uint4*)xp);
+    return hipGetLastError();
+}
+
+// out[t, :] = sum_j w[t, j] * y[row_of[t, j], :], fp32, slot order, one 16-byte store per lane.
+static __device__ inline float bf16lo(uint32_t u) { return __uint_as_float(u << 16); }
+static __device__ inline float bf16hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+static __device__ inline uint32_t pack_bf16x2(float a, float b) {
+    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+    ua += 0x7FFFu + ((ua >> 16) & 1u);
+    ub += 0x7FFFu + ((ub >> 16) & 1u);
+    return (ua >> 16) | (ub & 0xFFFF0000u);
+}
+
+__global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y,
+                                                      const int32_t* __restrict__ row_of,
+                                                      const float* __restrict__ w, int T, int k,
+                                                      int chunks /* d / 8 */, uint4* __restrict__ out) {
+    const int chunks_per_block = blockDim.x;
+    const int blocks_per_row = (chunks + chunks_per_block - 1) / chunks_per_block;
+    const int t = blockIdx.x / blocks_per_row;
+    const int c = (blockIdx.x % blocks_per_row) * chunks_per_block + threadIdx.x;
+    if (t >= T || c >= chunks) return;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < k; ++j) {
+        int r = row_of[(size_t)t * k + j];
+        if (r < 0) continue;
+        float g = w[(size_t)t * k + j];
+        uint4 v = y[(size_t)r * chunks + c];
+        acc[0] += g * bf16lo(v.x); acc[1] += g * bf16hi(v.x);
+        acc[2] += g * bf16lo(v.y); acc[3] += g * bf16hi(v.y);
+        acc[4] += g * bf16lo(v.z); acc[5] += g * bf16hi(v.z);
+        acc[6] += g * bf16lo(v.w); acc[7] += g * bf16hi(v.w);
+    }
+    uint4 o;
+    o.x = pack_bf16x2(acc[0], acc[1]);
+    o.y = pack_bf16x2(acc[2], acc[3]);
+    o.z = pack_bf16x2(acc[4], acc[5]);
+    o.w = pack_bf16x2(acc[6], acc[7]);
+    out[(size_t)t * chunks + c] = o;
+}
+
+hipError_t launch_combine(const uint16_t* y, const int32_t* row_of, const float* w, int T, int k, int d,
+                          uint16_t* out, hipStream_t st) {
+    int chunks = d / 8;
+    int threads = chunks >= 256 ? 256 : (chunks + 63) / 64 * 64;
+    int blocks_per_row = (chunks + threads - 1) / threads;
+    hipLaunchKernelGGL(combine_kernel, dim3(T * blocks_per_row), dim3(threads), 0, st, (const uint4*)y, row_of,
+                       w, T, k, chunks, (uint4*)out);
+    return hipGetLastError();
+}
