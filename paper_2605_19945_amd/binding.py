@@ -70,6 +70,9 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships its own HIP runtime; import it first so that the library binds to that one
+    # instance instead of bringing a second runtime into the process.
+    import torch  # noqa: F401
     path = library_path()
     if not os.path.exists(path):
         raise RuntimeError(f"{path} is missing: build it with `python -m paper_2605_19945_amd.build` "
