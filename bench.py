@@ -119,7 +119,7 @@ def main():
     ap.add_argument("--workload", default="mixtral_T4096")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--tile-class", type=int, default=-1)
-    ap.add_argument("--cpu-sample-tokens", type=int, default=384)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--curve", action="store_true")
     ap.add_argument("--curve-loads", default="512,1024,2048,4096,8192")

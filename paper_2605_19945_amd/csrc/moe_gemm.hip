@@ -42,9 +42,9 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     static_assert(!SWIGLU || FN % 2 == 0, "SwiGLU needs gate/up block pairs in one wave");
     static_assert(BM % RPP == 0 && BN % RPP == 0 && XPASS >= 1 && WPASS >= 1, "staging shape");
     static_assert(BK == 32 || BK == 64, "BK");
-    constexpr int STAGE = (BM + BN) * CH;  // uint4 per stage
+    constexpr int STAGE = (BM + BN) * CH;  // 16-byte chunks per stage
 
-    extern __shared__ uint4 lds[];  // [2][STAGE]: X rows then W rows
+    extern __shared__ u32x4_t lds[];  // [2][STAGE]: X rows then W rows
 
     const TileDesc td = table[blockIdx.x];
     if (td.rows <= 0) return;
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     const int lc = tid % CH, lr = tid / CH;
 
     // ---- per-thread staging sources (fixed over the K loop) ------------------------------------
-    const uint4* xsrc[XPASS];
+    const u32x4_t* xsrc[XPASS];
     int xdst[XPASS];
 #pragma unroll
     for (int p = 0; p < XPASS; ++p) {
@@ -62,17 +62,17 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
         int rr = r < td.rows ? r : td.rows - 1;
         int grow = td.row0 + rr;
         if (row_map != nullptr) grow = row_map[grow];
-        xsrc[p] = (const uint4*)(X + (size_t)grow * ldx) + lc;
+        xsrc[p] = (const u32x4_t*)(X + (size_t)grow * ldx) + lc;
         xdst[p] = r * CH + (lc ^ ((r >> SWZ_SHIFT) & (CH - 1)));
     }
-    const uint4* wsrc[WPASS];
+    const u32x4_t* wsrc[WPASS];
     int wdst[WPASS];
 #pragma unroll
     for (int p = 0; p < WPASS; ++p) {
         int r = lr + p * RPP;
         int n = td.n0 + r;
         if (n >= Np) n = Np - 1;
-        wsrc[p] = (const uint4*)(Wp + ((size_t)td.expert * Np + n) * K) + lc;
+        wsrc[p] = (const u32x4_t*)(Wp + ((size_t)td.expert * Np + n) * K) + lc;
         wdst[p] = BM * CH + r * CH + (lc ^ ((r >> SWZ_SHIFT) & (CH - 1)));
     }
 
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
     const int KT = K / BK;
-    uint4 xreg[XPASS], wreg[WPASS];
+    u32x4_t xreg[XPASS], wreg[WPASS];
 #pragma unroll
     for (int p = 0; p < XPASS; ++p) xreg[p] = xsrc[p][0];
 #pragma unroll
@@ -106,8 +106,8 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
 #pragma unroll
             for (int p = 0; p < WPASS; ++p) wreg[p] = wsrc[p][(size_t)(kt + 1) * CH];
         }
-        const uint4* xs = lds + cur * STAGE;
-        const uint4* ws = xs + BM * CH;
+        const u32x4_t* xs = lds + cur * STAGE;
+        const u32x4_t* ws = xs + BM * CH;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             const int c = kk * 2 + fhalf;
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
         }
         if (kt + 1 < KT) {
-            uint4* nxt = lds + (cur ^ 1) * STAGE;
+            u32x4_t* nxt = lds + (cur ^ 1) * STAGE;
 #pragma unroll
             for (int p = 0; p < XPASS; ++p) nxt[xdst[p]] = xreg[p];
 #pragma unroll
