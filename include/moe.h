@@ -145,12 +145,15 @@ moe_status moe_layer_forward(moe_ctx* ctx, const void* x, const void* router_pac
  * Blocks until the last of those calls has completed.  ms: host, MOE_NUM_STAGES floats. */
 moe_status moe_stage_times(moe_ctx* ctx, float* ms /* host */);
 
-/* Token-tile height of the expert GEMMs for this shape: per-expert row counts are rounded up to
- * a multiple of it, which sets the staircase of the latency-vs-load curve (paper Sec. 3.3.2). */
+/* Largest token-tile height of the expert GEMMs for this shape.  An expert's rows are cut into
+ * ceil(n / height) tiles of nearly equal height (multiples of 32 rows); the work per tile grows in
+ * steps of 32 rows per wavefront row, which sets the staircase of the latency-vs-load curve (the
+ * paper's tile boundaries, Sec. 3.3.2). */
 int32_t moe_tile_rows(const moe_ctx* ctx);
 
-/* Tuning hook: force the token-tile class of the expert GEMMs (0: 32 rows, 1: 64, 2: 128, 3: 256;
- * -1: choose from the expected rows per expert, the default). */
+/* Tuning hook: force the token-tile class of the expert GEMMs (0: up to 32 rows per tile, 1: 64,
+ * 2: 128, 3: 320; higher values select alternative kernels kept for tuning runs; -1: choose from
+ * the expected rows per expert, the default). */
 moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
 
 /* Device pointers into the workspace holding the intermediates of the most recent

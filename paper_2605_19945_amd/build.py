@@ -26,6 +26,8 @@ def _hipcc() -> str:
 def build(verbose: bool = False, extra_flags=()) -> str:
     os.makedirs(BUILD, exist_ok=True)
     hipcc = _hipcc()
+    if os.path.exists(LIB):
+        os.remove(LIB)          # never leave a stale library behind a failed build
 
     def compile_one(src):
         obj = os.path.join(BUILD, src.replace(".hip", ".o"))

@@ -56,7 +56,7 @@ Layout make_layout(const moe_shape* s) {
     }
     L.table1 = take((size_t)L.table1_cap * sizeof(TileDesc));
     L.table2 = take((size_t)L.table2_cap * sizeof(TileDesc));
-    L.H = take((size_t)L.rows_cap * s->f * 2);
+    L.H = take((size_t)L.rows_cap * moe_ld_pad(s->f) * 2);
     L.Y = take((size_t)L.rows_cap * s->d * 2);
     L.total = o;
     return L;
@@ -110,7 +110,7 @@ size_t moe_packed_router_bytes(const moe_shape* s) {
 
 size_t moe_packed_weight_bytes(const moe_shape* s) {
     if (!shape_ok(s)) return 0;
-    return (size_t)3 * s->E_local * s->d * s->f * 2;
+    return (size_t)s->E_local * ((size_t)2 * s->f * moe_ld_pad(s->d) + (size_t)s->d * moe_ld_pad(s->f)) * 2;
 }
 
 moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t bytes) {
@@ -251,7 +251,7 @@ static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t*
     if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
     c->last_cls = cls;
     const uint16_t* w13p = packed;
-    const uint16_t* w2p = packed + (size_t)s.E_local * 2 * s.f * s.d;
+    const uint16_t* w2p = packed + (size_t)s.E_local * 2 * s.f * moe_ld_pad(s.d);
     hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM1], st);

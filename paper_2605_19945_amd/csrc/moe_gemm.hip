@@ -8,14 +8,18 @@
 // Design (CDNA4):
 //   * work item = BM rows of ONE expert x BN packed weight rows; the list of work items is built
 //     on the device from the per-expert offsets (no host sync), experts with no rows get none,
-//     the last row tile of an expert is partial (loads clamped, stores masked) -- no padding to
-//     the largest expert.
-//   * both operands are reduction-contiguous (weights are pre-transposed at load time), staged
-//     through LDS in 16-byte chunks with an XOR swizzle, double buffered over the K loop;
+//     the last row tile of an expert is partial (loads clamped or skipped, stores masked) -- no
+//     padding to the largest expert.
+//   * both operands are reduction-contiguous (weights are pre-transposed at load time), staged in
+//     LDS in 16-byte chunks with an XOR swizzle, multi-buffered over the K loop;
 //     v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the first operand and the TOKEN rows as
 //     the second, so a lane's accumulator holds 4 consecutive output columns of one token row.
 //   * work items are ordered so that the workgroups running concurrently on one XCD (ids equal
 //     modulo 8) share weight panels and row panels through that XCD's L2.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "moe_internal.h"
 
 static __device__ inline uint32_t pack2_bf16(float a, float b) {
@@ -26,120 +30,13 @@ static __device__ inline uint32_t pack2_bf16(float a, float b) {
 }
 static __device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
 
-template <int BM, int BN, int BK, int WM, int WN, bool SWIGLU>
-__global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
-    const uint16_t* __restrict__ X, int ldx, const int32_t* __restrict__ row_map,
-    const uint16_t* __restrict__ Wp, int Np, int K, uint16_t* __restrict__ C, int ldc,
-    const TileDesc* __restrict__ table) {
-    constexpr int NT = WM * WN * 64;
-    constexpr int TM = BM / WM, TN = BN / WN;  // wave tile: TM token rows x TN weight rows
-    constexpr int FM = TM / 32, FN = TN / 32;  // 32x32 accumulator blocks per wave
-    constexpr int CH = BK / 8;                 // 16-byte chunks per staged row
-    constexpr int RPP = NT / CH;               // rows staged per pass of the whole workgroup
-    constexpr int XPASS = BM / RPP, WPASS = BN / RPP;
-    constexpr int SWZ_SHIFT = (CH == 8) ? 0 : (CH == 4 ? 1 : 2);
-    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 blocks");
-    static_assert(!SWIGLU || FN % 2 == 0, "SwiGLU needs gate/up block pairs in one wave");
-    static_assert(BM % RPP == 0 && BN % RPP == 0 && XPASS >= 1 && WPASS >= 1, "staging shape");
-    static_assert(BK == 32 || BK == 64, "BK");
-    constexpr int STAGE = (BM + BN) * CH;  // 16-byte chunks per stage
-
-    extern __shared__ u32x4_t lds[];  // [2][STAGE]: X rows then W rows
-
-    const TileDesc td = table[blockIdx.x];
-    if (td.rows <= 0) return;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int lc = tid % CH, lr = tid / CH;
-
-    // ---- per-thread staging sources (fixed over the K loop) ------------------------------------
-    const u32x4_t* xsrc[XPASS];
-    int xdst[XPASS];
-#pragma unroll
-    for (int p = 0; p < XPASS; ++p) {
-        int r = lr + p * RPP;
-        int rr = r < td.rows ? r : td.rows - 1;
-        int grow = td.row0 + rr;
-        if (row_map != nullptr) grow = row_map[grow];
-        xsrc[p] = (const u32x4_t*)(X + (size_t)grow * ldx) + lc;
-        xdst[p] = r * CH + (lc ^ ((r >> SWZ_SHIFT) & (CH - 1)));
-    }
-    const u32x4_t* wsrc[WPASS];
-    int wdst[WPASS];
-#pragma unroll
-    for (int p = 0; p < WPASS; ++p) {
-        int r = lr + p * RPP;
-        int n = td.n0 + r;
-        if (n >= Np) n = Np - 1;
-        wsrc[p] = (const u32x4_t*)(Wp + ((size_t)td.expert * Np + n) * K) + lc;
-        wdst[p] = BM * CH + r * CH + (lc ^ ((r >> SWZ_SHIFT) & (CH - 1)));
-    }
-
-    f32x16_t acc[FN][FM];
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-        for (int b = 0; b < FM; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-    const int KT = K / BK;
-    u32x4_t xreg[XPASS], wreg[WPASS];
-#pragma unroll
-    for (int p = 0; p < XPASS; ++p) xreg[p] = xsrc[p][0];
-#pragma unroll
-    for (int p = 0; p < WPASS; ++p) wreg[p] = wsrc[p][0];
-#pragma unroll
-    for (int p = 0; p < XPASS; ++p) lds[xdst[p]] = xreg[p];
-#pragma unroll
-    for (int p = 0; p < WPASS; ++p) lds[wdst[p]] = wreg[p];
-    __syncthreads();
-
-    // fragment rows of this lane inside the staged tile
+// Epilogue shared by the GEMM kernels.  Accumulator element v of lane l in block (a, b) is
+//   weight row  a*32 + 8*(v/4) + 4*(l/32) + v%4,   token row  b*32 + l%32,
+// so a lane owns 4 consecutive output columns of one token row per accumulator quad.
+template <int FM, int FN, int TM, int TN, bool SWIGLU>
+static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileDesc& td, int Np,
+                                            uint16_t* __restrict__ C, int ldc, int wm, int wn, int lane) {
     const int frow = lane & 31, fhalf = lane >> 5;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < KT) {
-#pragma unroll
-            for (int p = 0; p < XPASS; ++p) xreg[p] = xsrc[p][(size_t)(kt + 1) * CH];
-#pragma unroll
-            for (int p = 0; p < WPASS; ++p) wreg[p] = wsrc[p][(size_t)(kt + 1) * CH];
-        }
-        const u32x4_t* xs = lds + cur * STAGE;
-        const u32x4_t* ws = xs + BM * CH;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int c = kk * 2 + fhalf;
-            bf16x8_t xf[FM], wf[FN];
-#pragma unroll
-            for (int b = 0; b < FM; ++b) {
-                int r = wm * TM + b * 32 + frow;
-                xf[b] = __builtin_bit_cast(bf16x8_t, xs[r * CH + (c ^ ((r >> SWZ_SHIFT) & (CH - 1)))]);
-            }
-#pragma unroll
-            for (int a = 0; a < FN; ++a) {
-                int r = wn * TN + a * 32 + frow;
-                wf[a] = __builtin_bit_cast(bf16x8_t, ws[r * CH + (c ^ ((r >> SWZ_SHIFT) & (CH - 1)))]);
-            }
-#pragma unroll
-            for (int a = 0; a < FN; ++a)
-#pragma unroll
-                for (int b = 0; b < FM; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf[b], acc[a][b], 0, 0, 0);
-        }
-        if (kt + 1 < KT) {
-            u32x4_t* nxt = lds + (cur ^ 1) * STAGE;
-#pragma unroll
-            for (int p = 0; p < XPASS; ++p) nxt[xdst[p]] = xreg[p];
-#pragma unroll
-            for (int p = 0; p < WPASS; ++p) nxt[wdst[p]] = wreg[p];
-        }
-        __syncthreads();
-    }
-
-    // ---- epilogue: accumulator element v of lane l in block (a, b) is
-    //      weight row  a*32 + 8*(v/4) + 4*(l/32) + v%4,  token row  b*32 + l%32 --------------------
 #pragma unroll
     for (int b = 0; b < FM; ++b) {
         const int trow = wm * TM + b * 32 + frow;
@@ -157,10 +54,10 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
 #pragma unroll
                     for (int v = 0; v < 4; ++v)
                         h[v] = silu_f32(acc[2 * a2][b][4 * q + v]) * acc[2 * a2 + 1][b][4 * q + v];
-                    uint2 o;
+                    u32x2_t o;
                     o.x = pack2_bf16(h[0], h[1]);
                     o.y = pack2_bf16(h[2], h[3]);
-                    *(uint2*)(crow + hcol + 8 * q) = o;
+                    *(u32x2_t*)(crow + hcol + 8 * q) = o;
                 }
             }
         } else {
@@ -170,10 +67,10 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
                 if (col >= Np) continue;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    uint2 o;
+                    u32x2_t o;
                     o.x = pack2_bf16(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]);
                     o.y = pack2_bf16(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                    *(uint2*)(crow + col + 4 * fhalf + 8 * q) = o;
+                    *(u32x2_t*)(crow + col + 4 * fhalf + 8 * q) = o;
                 }
             }
         }
@@ -181,10 +78,204 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// Device-side work list.  Work-item id b runs on XCD b % 8 (workgroups are dealt round-robin to
-// the 8 XCDs); XCD x owns the weight-row tiles x, x+8, ...; inside an XCD the order is
-// expert-major, then weight-row tile, then row tile (fastest), so the ~32 workgroups resident on
-// an XCD cover all row tiles of one expert times a handful of its weight tiles.
+// The GEMM kernel.  Operands go global -> LDS with global_load_lds_dwordx4 (no VGPR staging, no
+// ds_write): one wave-level load writes 64 lanes x 16 bytes contiguously at a wave-uniform LDS
+// address (lane l lands at base + 16*l), so the bank-conflict-avoiding XOR swizzle is applied on
+// the *global* side: the lane that owns physical chunk p of a row fetches logical chunk
+// p ^ swz(row).  NSTAGE-deep LDS ring, prefetch distance D = NSTAGE-1, one barrier per K step:
+//   wait own loads of stage kt | barrier | issue loads of stage kt+D into the slot read at kt-1 |
+//   MFMAs on stage kt.
+// SPREAD = 1 issues the next stage's loads in slices between the MFMA sub-steps instead of one
+// burst after the barrier.
+// Row tiles have a run-time height (a multiple of 32 rows up to BM, the last one of an expert
+// possibly ragged): 32-row blocks past the last valid row are neither loaded nor multiplied.
+// ------------------------------------------------------------------------------------------------
+template <int CH>
+static __device__ inline int swz_of(int r) {
+    // LDS: 64 banks x 4 B; a ds_read_b128 is served 16 lanes (256 B) per cycle.  The 16 rows a
+    // lane group reads at one logical chunk must land in 16 distinct 16-byte slots of a 256-byte
+    // bank line: rows sharing a bank-line position (r mod (16/CH)) get distinct XOR masks.
+    return (CH == 8) ? ((r >> 1) & 7) : ((r >> 2) & 3);
+}
+
+template <int N>
+static __device__ inline void wait_vmcnt() {
+    // s_waitcnt vmcnt(N) only: expcnt = 7, lgkmcnt = 15 are left unconstrained (gfx9 encoding)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int SPREAD, bool SWIGLU>
+__global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
+    const uint16_t* __restrict__ X, int ldx, const int32_t* __restrict__ row_map,
+    const uint16_t* __restrict__ Wp, int ldw, int Np, int K, uint16_t* __restrict__ C, int ldc,
+    const TileDesc* __restrict__ table) {
+    constexpr int NW = WM * WN;
+    constexpr int TM = BM / WM, TN = BN / WN;  // wave tile: TM token rows x TN weight rows
+    constexpr int FM = TM / 32, FN = TN / 32;  // 32x32 accumulator blocks per wave
+    constexpr int CH = BK / 8;                 // 16-byte chunks per staged row
+    constexpr int RPL = 64 / CH;               // rows covered by one wave-level load
+    constexpr int XPASS = BM / (NW * RPL), WPASS = BN / (NW * RPL);
+    constexpr int LPT = XPASS + WPASS;         // loads per thread per stage
+    constexpr int STAGE = (BM + BN) * CH;      // 16-byte chunks per stage
+    constexpr int D = NSTAGE - 1;
+    constexpr int KK = BK / 16;                // MFMA sub-steps per K step
+    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 blocks");
+    static_assert(!SWIGLU || FN % 2 == 0, "SwiGLU needs gate/up block pairs in one wave");
+    static_assert(BM % (NW * RPL) == 0 && BN % (NW * RPL) == 0, "staging shape");
+    static_assert(BK == 32 || BK == 64, "BK");
+    static_assert(NSTAGE >= 2 && NSTAGE <= 4 && D * LPT < 64, "pipeline depth");
+
+    extern __shared__ u32x4_t lds[];  // [NSTAGE][STAGE]: X rows then W rows
+
+    const TileDesc td = table[blockIdx.x];
+    if (td.rows <= 0) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it in an SGPR
+    const int wm = wave / WN, wn = wave % WN;
+    const int lrow = lane / CH, lphys = lane % CH;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int KT = K / BK;
+
+    // per-thread global sources (advance by BK elements per K step)
+    const uint16_t* xsrc[XPASS];
+    const uint16_t* wsrc[WPASS];
+#pragma unroll
+    for (int p = 0; p < XPASS; ++p) {
+        const int r = (p * NW + wave) * RPL + lrow;
+        const int rr = r < td.rows ? r : td.rows - 1;  // clamp: rows past the end are never stored
+        int grow = td.row0 + rr;
+        if (row_map != nullptr) grow = row_map[grow];
+        xsrc[p] = X + (size_t)grow * ldx + (lphys ^ swz_of<CH>(r)) * 8;
+    }
+#pragma unroll
+    for (int p = 0; p < WPASS; ++p) {
+        const int r = (p * NW + wave) * RPL + lrow;
+        int n = td.n0 + r;
+        if (n >= Np) n = Np - 1;
+        wsrc[p] = Wp + ((size_t)td.expert * Np + n) * ldw + (lphys ^ swz_of<CH>(r)) * 8;
+    }
+    // LDS fragment addresses of this lane (in 16-byte chunks) and their XOR masks
+    int xoff[FM], xswz[FM], woff[FN], wswz[FN];
+#pragma unroll
+    for (int b = 0; b < FM; ++b) {
+        const int r = wm * TM + b * 32 + frow;
+        xoff[b] = r * CH;
+        xswz[b] = swz_of<CH>(r);
+    }
+#pragma unroll
+    for (int a = 0; a < FN; ++a) {
+        const int r = wn * TN + a * 32 + frow;
+        woff[a] = BM * CH + r * CH;
+        wswz[a] = swz_of<CH>(r);
+    }
+
+    f32x16_t acc[FN][FM];
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    // wave-uniform extents of the valid part of the tile (in 32-row blocks / load passes)
+    const int rows32 = (td.rows + 31) & ~31;
+    const bool full = td.rows == BM;
+    int fm_valid = (rows32 - wm * TM) / 32;  // valid 32-row blocks of this wave
+    fm_valid = fm_valid < 0 ? 0 : (fm_valid > FM ? FM : fm_valid);
+
+    // loads [lo, hi) of the LPT loads that bring in stage kt (X passes first, then W passes);
+    // X passes whose rows all lie past the last valid 32-row block are skipped
+    auto issue = [&](int kt, auto lo_c, auto hi_c) {
+        constexpr int lo = decltype(lo_c)::value, hi = decltype(hi_c)::value;
+        u32x4_t* base = lds + (kt % NSTAGE) * STAGE;
+#pragma unroll
+        for (int q = lo; q < hi; ++q) {
+            if (q < XPASS) {
+                if ((q * NW + wave) * RPL < rows32)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(xsrc[q] + (size_t)kt * BK),
+                        (__attribute__((address_space(3))) void*)(base + (q * NW + wave) * RPL * CH), 16, 0, 0);
+            } else {
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(wsrc[q - XPASS] + (size_t)kt * BK),
+                    (__attribute__((address_space(3))) void*)(base + BM * CH + ((q - XPASS) * NW + wave) * RPL * CH),
+                    16, 0, 0);
+            }
+        }
+    };
+    using IC0 = std::integral_constant<int, 0>;
+    using ICL = std::integral_constant<int, LPT>;
+
+    // The K loop, specialised on the number of valid 32-row blocks of this wave: FMV >= 0 is a
+    // compile-time count (no per-MFMA branches); FMV < 0 reads it at run time.  Waves of one
+    // workgroup may take different specialisations; all of them execute one barrier per K step.
+    auto main_loop = [&](auto fmv_c) {
+        constexpr int FMV = decltype(fmv_c)::value;
+        auto live = [&](int b) { return FMV >= 0 ? b < FMV : b < fm_valid; };
+        const bool any = FMV >= 0 ? FMV > 0 : fm_valid > 0;
+#pragma unroll
+        for (int s = 0; s < D; ++s)
+            if (s < KT) issue(s, IC0{}, ICL{});
+
+        for (int kt = 0; kt < KT; ++kt) {
+            // loads that may stay in flight: those of the already issued stages after kt (the
+            // count per stage is only known at compile time for full tiles)
+            const int ahead = full ? min(D - 1, KT - 1 - kt) : 0;
+            if (ahead <= 0) wait_vmcnt<0>();
+            else if (ahead == 1) wait_vmcnt<LPT>();
+            else wait_vmcnt<2 * LPT>();
+            // barrier without the workgroup fence of __syncthreads(): the fence would wait for ALL
+            // outstanding loads (vmcnt(0)) and collapse the prefetch distance to one stage
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            const bool more = kt + D < KT;
+            if constexpr (SPREAD == 0) {
+                if (more) issue(kt + D, IC0{}, ICL{});
+            }
+            const u32x4_t* st = lds + (kt % NSTAGE) * STAGE;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const int c = kk * 2 + fhalf;
+                if constexpr (SPREAD == 1) {
+                    // feed the vector-memory pipe a slice of the next stage's loads per sub-step
+                    // (all but the last sub-step) instead of one burst right after the barrier
+                    constexpr int PH = KK > 1 ? KK - 1 : 1;
+                    if (more) {
+                        if (kk == 0) issue(kt + D, std::integral_constant<int, 0>{}, std::integral_constant<int, (LPT * 1) / PH>{});
+                        if (kk == 1 && PH > 1) issue(kt + D, std::integral_constant<int, (LPT * 1) / PH>{}, std::integral_constant<int, (LPT * 2) / PH>{});
+                        if (kk == 2 && PH > 2) issue(kt + D, std::integral_constant<int, (LPT * 2) / PH>{}, std::integral_constant<int, (LPT * 3) / PH>{});
+                    }
+                }
+                bf16x8_t wf[FN];
+#pragma unroll
+                for (int a = 0; a < FN; ++a)
+                    if (any) wf[a] = __builtin_bit_cast(bf16x8_t, st[woff[a] + (c ^ wswz[a])]);
+#pragma unroll
+                for (int b = 0; b < FM; ++b)
+                    if (live(b)) {
+                        bf16x8_t xf = __builtin_bit_cast(bf16x8_t, st[xoff[b] + (c ^ xswz[b])]);
+#pragma unroll
+                        for (int a = 0; a < FN; ++a)
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf, acc[a][b], 0, 0, 0);
+                    }
+            }
+        }
+    };
+    if (fm_valid == FM) main_loop(std::integral_constant<int, FM>{});
+    else if (FM > 1 && fm_valid == FM - 1) main_loop(std::integral_constant<int, (FM > 1 ? FM - 1 : 0)>{});
+    else main_loop(std::integral_constant<int, -1>{});
+
+    gemm_epilogue<FM, FN, TM, TN, SWIGLU>(acc, td, Np, C, ldc, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Device-side work list.  The rows of expert e are cut into ceil(n_e / bm) row tiles of nearly
+// equal height (a multiple of 32 rows, at most bm): an expert slightly larger than a multiple of
+// the tile height does not get a nearly empty extra tile, its rows are spread over taller tiles.
+// Work-item id b runs on XCD b % 8 (workgroups are dealt round-robin to the 8 XCDs); XCD x owns the
+// weight-row tiles x, x+8, ...; inside an XCD the order is expert-major, then weight-row tile, then
+// row tile (fastest), so the ~32 workgroups resident on an XCD cover all row tiles of one expert
+// times a handful of its weight tiles and share both through that XCD's L2.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict__ offsets, int E_local,
                                                        int bm, int bn, int nt1, int grid1,
@@ -192,6 +283,7 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                                                        TileDesc* __restrict__ t2) {
     __shared__ int32_t pre[257];  // exclusive prefix of row tiles per expert; pre[E_local] = total
     __shared__ int32_t off[257];
+    __shared__ int32_t scan[256];
     const int tid = threadIdx.x;
     int mt = 0;
     if (tid < E_local) {
@@ -199,7 +291,6 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
         mt = (n + bm - 1) / bm;
     }
     for (int i = tid; i <= E_local; i += 256) off[i] = offsets[i];
-    __shared__ int32_t scan[256];
     scan[tid] = mt;
     __syncthreads();
     for (int o = 1; o < 256; o <<= 1) {
@@ -223,7 +314,7 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
             TileDesc td;
             td.expert = 0; td.row0 = 0; td.rows = 0; td.n0 = 0;
             if (j < MT * cnt) {
-                // largest e with pre[e] * cnt <= j
+                // largest e with pre[e] * cnt <= j  (that expert has at least one row tile)
                 int lo = 0, hi = E_local;
                 while (hi - lo > 1) {
                     int mid = (lo + hi) >> 1;
@@ -234,9 +325,14 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                 const int r = j - pre[e] * cnt;
                 const int mi = r % mte, nl = r / mte;
                 const int e_rows = off[e + 1] - off[e];
+                // 32-row blocks of the expert, dealt evenly to its mte tiles
+                const int nblk = (e_rows + 31) / 32;
+                const int base = nblk / mte, rem = nblk % mte;
+                const int blk0 = mi * base + min(mi, rem);
+                const int nb = base + (mi < rem ? 1 : 0);
                 td.expert = e;
-                td.row0 = off[e] + mi * bm;
-                td.rows = min(bm, e_rows - mi * bm);
+                td.row0 = off[e] + blk0 * 32;
+                td.rows = min(nb * 32, e_rows - blk0 * 32);
                 td.n0 = (nl * 8 + x) * bn;
             }
             table[b] = td;
@@ -245,20 +341,34 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
 }
 
 // ------------------------------------------------------------------------------------------------
-// Host side: tile classes, plans, launches.
+// Host side: tile variants, plans, launches.
+// Variant ids 0..3 are the production token-tile classes (up to 32 / 64 / 128 / 320 rows); higher ids
+// are alternatives kept for tuning runs (moe_set_tile_class).
+//   V(id, BM, BN, BK, WM, WN, NSTAGE, SPREAD)
 // ------------------------------------------------------------------------------------------------
-struct ClassDef { int bm, bn, bk, wm, wn; };
-static const ClassDef kClass[GEMM_NUM_CLASSES] = {
-    {32, 256, 64, 1, 4},    // GEMM_BM32
-    {64, 256, 64, 1, 4},    // GEMM_BM64
-    {128, 128, 64, 2, 2},   // GEMM_BM128
-    {256, 256, 64, 2, 4},   // GEMM_BM256
+#define FOR_EACH_VARIANT(V)                \
+    V(0, 32, 256, 64, 1, 4, 4, 0)          \
+    V(1, 64, 256, 64, 1, 4, 3, 0)          \
+    V(2, 128, 128, 64, 2, 2, 3, 0)         \
+    V(3, 320, 256, 64, 2, 4, 2, 1)         \
+    V(4, 256, 256, 64, 2, 4, 2, 0)         \
+    V(5, 256, 256, 64, 2, 4, 2, 1)         \
+    V(6, 320, 256, 64, 2, 4, 2, 0)         \
+    V(7, 256, 128, 64, 4, 2, 3, 0)         \
+    V(8, 128, 256, 64, 2, 4, 3, 0)         \
+    V(9, 128, 256, 64, 1, 4, 3, 0)
+
+struct VariantDef { int bm, bn, bk, wm, wn, nstage; };
+static const VariantDef kVariant[GEMM_NUM_CLASSES] = {
+#define V(id, bm, bn, bk, wm, wn, ns, spread) {bm, bn, bk, wm, wn, ns},
+    FOR_EACH_VARIANT(V)
+#undef V
 };
 
-int gemm_class_rows(int cls) { return kClass[cls].bm; }
+int gemm_class_rows(int cls) { return kVariant[cls].bm; }
 
 int gemm_pick_class(double rows_per_expert) {
-    if (rows_per_expert > 384.0) return GEMM_BM256;
+    if (rows_per_expert > 384.0) return GEMM_BM320;
     if (rows_per_expert > 96.0) return GEMM_BM128;
     if (rows_per_expert > 40.0) return GEMM_BM64;
     return GEMM_BM32;
@@ -267,8 +377,8 @@ int gemm_pick_class(double rows_per_expert) {
 GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) {
     GemmPlan p;
     p.cls = cls;
-    p.bm = kClass[cls].bm;
-    p.bn = kClass[cls].bn;
+    p.bm = kVariant[cls].bm;
+    p.bn = kVariant[cls].bn;
     int64_t extra = n_rows_cap < E_local ? n_rows_cap : E_local;
     p.mt_max = (int)(n_rows_cap / p.bm + extra);
     p.nt1 = (2 * f + p.bn - 1) / p.bn;
@@ -278,28 +388,30 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) 
     return p;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool SW>
-static hipError_t set_attr_t() {
-    size_t smem = (size_t)2 * (BM + BN) * BK * 2;
-    return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, BN, BK, WM, WN, SW>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-}
-
-#define FOR_EACH_CLASS(M)      \
-    M(GEMM_BM32, 32, 256, 64, 1, 4)   \
-    M(GEMM_BM64, 64, 256, 64, 1, 4)   \
-    M(GEMM_BM128, 128, 128, 64, 2, 2) \
-    M(GEMM_BM256, 256, 256, 64, 2, 4)
+template <int BM, int BN, int BK, int WM, int WN, int NS, int SPREAD, bool SW>
+struct Variant {
+    static constexpr size_t smem = (size_t)NS * (BM + BN) * BK * 2;
+    static hipError_t set_attr() {
+        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SW>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    }
+    static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wp,
+                             int ldw, int Np, int K, uint16_t* C, int ldc, const TileDesc* table, hipStream_t st) {
+        hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SW>), dim3(grid),
+                           dim3(WM * WN * 64), smem, st, X, ldx, row_map, Wp, ldw, Np, K, C, ldc, table);
+        return hipGetLastError();
+    }
+};
 
 hipError_t gemm_init_attributes() {
     hipError_t err;
-#define M(cls, bm, bn, bk, wm, wn)                                       \
-    err = set_attr_t<bm, bn, bk, wm, wn, true>();                        \
-    if (err != hipSuccess) return err;                                   \
-    err = set_attr_t<bm, bn, bk, wm, wn, false>();                       \
+#define V(id, bm, bn, bk, wm, wn, ns, spread)                             \
+    err = Variant<bm, bn, bk, wm, wn, ns, spread, true>::set_attr();        \
+    if (err != hipSuccess) return err;                                    \
+    err = Variant<bm, bn, bk, wm, wn, ns, spread, false>::set_attr();       \
     if (err != hipSuccess) return err;
-    FOR_EACH_CLASS(M)
-#undef M
+    FOR_EACH_VARIANT(V)
+#undef V
     return hipSuccess;
 }
 
@@ -314,24 +426,15 @@ hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_loca
     return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool SW>
-static hipError_t gemm_launch_t(int grid, const uint16_t* X, int ldx, const int32_t* row_map,
-                                const uint16_t* Wp, int Np, int K, uint16_t* C, int ldc, const TileDesc* table,
-                                hipStream_t st) {
-    size_t smem = (size_t)2 * (BM + BN) * BK * 2;
-    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, WM, WN, SW>), dim3(grid), dim3(WM * WN * 64), smem, st,
-                       X, ldx, row_map, Wp, Np, K, C, ldc, table);
-    return hipGetLastError();
-}
-
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13p, int d, int f, uint16_t* H, const TileDesc* table, hipStream_t st) {
     if (p.grid1 <= 0) return hipSuccess;
     switch (p.cls) {
-#define M(cls, bm, bn, bk, wm, wn) \
-    case cls: return gemm_launch_t<bm, bn, bk, wm, wn, true>(p.grid1, X, ldx, row_map, W13p, 2 * f, d, H, f, table, st);
-        FOR_EACH_CLASS(M)
-#undef M
+#define V(id, bm, bn, bk, wm, wn, ns, spread) \
+    case id:                                \
+        return Variant<bm, bn, bk, wm, wn, ns, spread, true>::launch(p.grid1, X, ldx, row_map, W13p, moe_ld_pad(d), 2 * f, d, H, moe_ld_pad(f), table, st);
+        FOR_EACH_VARIANT(V)
+#undef V
     }
     return hipErrorInvalidValue;
 }
@@ -340,10 +443,11 @@ hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2
                         const TileDesc* table, hipStream_t st) {
     if (p.grid2 <= 0) return hipSuccess;
     switch (p.cls) {
-#define M(cls, bm, bn, bk, wm, wn) \
-    case cls: return gemm_launch_t<bm, bn, bk, wm, wn, false>(p.grid2, H, f, nullptr, W2p, d, f, Y, d, table, st);
-        FOR_EACH_CLASS(M)
-#undef M
+#define V(id, bm, bn, bk, wm, wn, ns, spread) \
+    case id:                                \
+        return Variant<bm, bn, bk, wm, wn, ns, spread, false>::launch(p.grid2, H, moe_ld_pad(f), nullptr, W2p, moe_ld_pad(f), d, f, Y, d, table, st);
+        FOR_EACH_VARIANT(V)
+#undef V
     }
     return hipErrorInvalidValue;
 }

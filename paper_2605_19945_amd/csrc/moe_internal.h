@@ -20,7 +20,7 @@ struct TileDesc {
 };
 
 // Token-tile classes of the grouped GEMM.
-enum GemmClass { GEMM_BM32 = 0, GEMM_BM64 = 1, GEMM_BM128 = 2, GEMM_BM256 = 3, GEMM_NUM_CLASSES };
+enum GemmClass { GEMM_BM32 = 0, GEMM_BM64 = 1, GEMM_BM128 = 2, GEMM_BM320 = 3, GEMM_NUM_CLASSES = 10 };
 
 struct GemmPlan {
     int cls;         // GemmClass
@@ -58,6 +58,10 @@ struct moe_ctx {
 };
 
 static inline int64_t moe_round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+// Leading dimension (elements) of a K-contiguous operand the library lays out itself (packed
+// weights, the intermediate H): rows are padded by 128 bytes so that the rows of a tile, which
+// are all read at the same K offset, do not fall on one L2 channel when K*2 is a power of two.
+static __host__ __device__ inline int moe_ld_pad(int K) { return K + 64; }
 static inline int moe_router_rows(int E) {  // packed router rows: multiple of 16, power-of-two blocks
     int nb = (E + 15) / 16;
     int p = 1;

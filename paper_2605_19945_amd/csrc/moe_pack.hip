@@ -1,7 +1,8 @@
 // Load-time repacking of the expert weights (the analogue of the paper's deployment step, which
 // places each expert's weights on its GPU once, Sec. 3.3.4).  Not on the hot path.
 //
-// Packed layout (bf16): [ W13p : E_local x 2f x d ][ W2p : E_local x d x f ]
+// Packed layout (bf16): [ W13p : E_local x 2f x ld(d) ][ W2p : E_local x d x ld(f) ], ld(K) = K + 64
+// (rows padded by 128 bytes, see moe_ld_pad)
 //   W13p[e][(c/32)*64 + s*32 + c%32][i] = (s == 0 ? W1 : W3)[e][i][c]     (c < f, i < d)
 //   W2p [e][c][j]                       = W2[e][j][c]                     (c < d, j < f)
 // i.e. every matrix is transposed so that the reduction dimension is contiguous, and W1/W3 are
@@ -19,20 +20,21 @@ __global__ __launch_bounds__(256) void transpose_pack_kernel(const uint16_t* __r
     const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const uint16_t* src = in + (size_t)e * R * C;
-    uint16_t* dst = out + (size_t)e * out_rows * R;
+    const int ld = moe_ld_pad(R);
+    uint16_t* dst = out + (size_t)e * out_rows * ld;
     for (int rr = ty; rr < 64; rr += 4) tile[rr][tx] = src[(size_t)(r0 + rr) * C + c0 + tx];
     __syncthreads();
     for (int cc = ty; cc < 64; cc += 4) {
         int c = c0 + cc;
         int orow = interleave ? (c / 32) * 64 + slot * 32 + (c % 32) : c;
-        dst[(size_t)orow * R + r0 + tx] = tile[tx][cc];
+        dst[(size_t)orow * ld + r0 + tx] = tile[tx][cc];
     }
 }
 
 hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uint16_t* W2, int E_local, int d,
                                int f, uint16_t* packed, hipStream_t st) {
     uint16_t* w13p = packed;
-    uint16_t* w2p = packed + (size_t)E_local * 2 * f * d;
+    uint16_t* w2p = packed + (size_t)E_local * 2 * f * moe_ld_pad(d);
     dim3 g13(f / 64, d / 64, E_local), g2(d / 64, f / 64, E_local);
     hipLaunchKernelGGL(transpose_pack_kernel, g13, dim3(256), 0, st, W1, d, f, w13p, 2 * f, 1, 0);
     hipLaunchKernelGGL(transpose_pack_kernel, g13, dim3(256), 0, st, W3, d, f, w13p, 2 * f, 1, 1);
