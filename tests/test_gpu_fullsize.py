@@ -1,0 +1,140 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Routing outputs are checked for every token; layer / expert outputs on a seeded sample of rows the
+oracle evaluates one by one (each output row depends only on its own token, its experts and the
+weights), always including rows at the start and the end of expert segments, where ragged tiles
+and masked stores live."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import moe_oracle as orc
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+_weights_cache = {}
+
+
+def weights_for(key, E_local, d, f):
+    """Expert weights are drawn once per shape (seed 0) and shared by the tests that use them."""
+    if key not in _weights_cache:
+        _weights_cache.clear()            # keep at most one multi-GB set on the host
+        _weights_cache[key] = wl.expert_weights(0, E_local, d, f)
+    return _weights_cache[key]
+
+
+@pytest.fixture(scope="module")
+def moe():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    import paper_2605_19945_amd as m
+    m.load_library()
+    return m
+
+
+def sample_tokens(T, idx, offsets, row_of, n_random, seed):
+    """Random tokens plus the tokens sitting in the first and last rows of every expert segment."""
+    rng = np.random.default_rng(seed)
+    toks = set(rng.choice(T, size=min(n_random, T), replace=False).tolist())
+    tok_of_row = {}
+    for t in range(T):
+        for r in row_of[t]:
+            if r >= 0:
+                tok_of_row[int(r)] = t
+    for e in range(len(offsets) - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        for r in list(range(lo, min(lo + 3, hi))) + list(range(max(lo, hi - 3), hi)):
+            toks.add(tok_of_row[r])
+    return np.array(sorted(toks), dtype=np.int64)
+
+
+def run_full_layer(moe, inp, n_random=192, max_near_frac=0.02):
+    import torch
+    s = inp.shape
+    print(f"full-size layer {inp.name}: T={s.T} d={s.d} f={s.f} E={s.E} k={s.k} local=[{s.e_lo},{s.e_lo + s.E_local})",
+          flush=True)
+    ctx = moe.MoEContext(s.T, s.d, s.f, s.E, s.k, s.e_lo, s.E_local)
+    x = gu.to_dev_bf16(inp.x)
+    rp = ctx.moe_pack_router(gu.to_dev(inp.Wg))
+    bias = gu.to_dev(inp.bias) if inp.bias is not None else None
+    W1, W3, W2 = gu.to_dev_bf16(inp.W1), gu.to_dev_bf16(inp.W3), gu.to_dev_bf16(inp.W2)
+    packed = ctx.moe_pack_weights(W1, W3, W2)
+    torch.cuda.synchronize()
+    del W1, W3, W2
+    counts = torch.empty(s.E, dtype=torch.int32, device="cuda")
+    out = ctx.moe_layer_forward(x, rp, bias, packed, counts_out=counts)
+    torch.cuda.synchronize()
+    idx, w, offsets, row_of = (t.cpu().numpy() for t in ctx.moe_layer_intermediates(s.T))
+    counts = counts.cpu().numpy()
+    # routing: every token
+    logits = orc.router_logits(inp.x, inp.Wg, inp.bias)
+    near = gu.check_routing(orc, logits, s.k, idx, w, counts)
+    assert near <= max(3, max_near_frac * s.T), f"{near} near-tie tokens"
+    # dispatch: every assignment, bit exact given the GPU's indices
+    r_off, r_row, _ = orc.permutation(idx, s.E, s.e_lo, s.E_local)
+    assert (offsets == r_off).all() and (row_of == r_row).all()
+    assert counts.sum() == s.T * s.k
+    # outputs: sampled tokens
+    toks = sample_tokens(s.T, idx, offsets, row_of, n_random, seed=s.T)
+    ref = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k, e_lo=s.e_lo, tokens=toks, idx=idx)
+    row_rel, glob = gu.check_output(gu.f64_of_bf16(out)[toks], ref["out"], what=inp.name)
+    n_e = np.diff(offsets)
+    print(f"   near-ties {near}/{s.T}; {len(toks)} tokens checked: row_rel {row_rel:.2e}, glob {glob:.2e}; "
+          f"rows/expert min {n_e.min()} median {int(np.median(n_e))} max {n_e.max()}, "
+          f"experts with <32 rows: {(n_e < 32).sum()}, tile rows {ctx.moe_tile_rows()}", flush=True)
+    ctx.close()
+    return counts
+
+
+def test_mixtral_T4096_layer(moe):
+    weights = weights_for("mixtral", wl.MIXTRAL_E, wl.MIXTRAL_D, wl.MIXTRAL_F)
+    counts = run_full_layer(moe, wl.mixtral(4096, 0, weights=weights))
+    assert counts.min() > 900 and counts.max() < 1150          # near-uniform load
+
+
+@pytest.mark.parametrize("T", [512, 8192])
+def test_mixtral_skewed_layer(moe, T):
+    weights = weights_for("mixtral", wl.MIXTRAL_E, wl.MIXTRAL_D, wl.MIXTRAL_F)
+    counts = run_full_layer(moe, wl.mixtral_skewed(T, 0, weights=weights))
+    share = counts / counts.sum()
+    assert abs(share[0] - 0.30) < 0.04 and abs(share[1] - 0.30) < 0.04
+
+
+def test_fine_grained_T8192_layer(moe):
+    weights = weights_for("fine", 128, 2048, 768)
+    run_full_layer(moe, wl.fine_grained(8192, 0, weights=weights), n_random=128)
+
+
+@pytest.mark.parametrize("T", [128, 2048])
+def test_ep_share_layer(moe, T):
+    weights = weights_for("ep", wl.EP_ELOCAL, wl.EP_D, wl.EP_F)
+    run_full_layer(moe, wl.ep_share_layer(T, 0, weights=weights), n_random=96)
+
+
+@pytest.mark.parametrize("N", [256, 4096, 16384])
+def test_ep_share_direct_groups(moe, N):
+    """The already-routed form: rows grouped by local expert, Zipf(1.0) group sizes."""
+    import torch
+    W1, W3, W2 = weights_for("ep", wl.EP_ELOCAL, wl.EP_D, wl.EP_F)
+    xp, off = wl.ep_share_groups(N, 0)
+    print(f"full-size direct groups N={N}: rows/expert {np.diff(off).tolist()}", flush=True)
+    ctx = moe.MoEContext(N, wl.EP_D, wl.EP_F, wl.EP_ELOCAL, 1)
+    packed = ctx.moe_pack_weights(gu.to_dev_bf16(W1), gu.to_dev_bf16(W3), gu.to_dev_bf16(W2))
+    y = torch.full((N, wl.EP_D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ctx.moe_grouped_ffn(gu.to_dev_bf16(xp), gu.to_dev(off), N, packed, y=y)
+    torch.cuda.synchronize()
+    got = gu.f64_of_bf16(y)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(N)
+    rows = set(rng.choice(N, size=min(160, N), replace=False).tolist())
+    for e in range(wl.EP_ELOCAL):
+        lo, hi = int(off[e]), int(off[e + 1])
+        rows.update(range(lo, min(lo + 2, hi)))
+        rows.update(range(max(lo, hi - 2), hi))
+    rows = np.array(sorted(rows), dtype=np.int64)
+    ref = orc.grouped_ffn(xp, off, W1, W3, W2, rows=rows)
+    row_rel, glob = gu.check_output(got[rows], ref, what=f"direct N={N}")
+    print(f"   {len(rows)} rows checked: row_rel {row_rel:.2e}, glob {glob:.2e}, tile rows {ctx.moe_tile_rows()}", flush=True)
+    ctx.close()

@@ -19,4 +19,6 @@ from .gen import (  # noqa: F401
     ep_share_layer,
     ep_share_groups,
     custom,
+    MIXTRAL_D, MIXTRAL_F, MIXTRAL_E, MIXTRAL_K,
+    EP_D, EP_F, EP_E, EP_K, EP_ELO, EP_ELOCAL,
 )
