@@ -45,6 +45,21 @@ def make_workload(name, seed, weights):
     raise SystemExit(f"unknown workload {name}")
 
 
+def profiled_traffic(workload, kernel):
+    """HBM-side bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    of this workload (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration); None if no
+    summary exists for this workload."""
+    path = os.path.join(ROOT, "profiles", f"gemm_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def time_layer(ctx, x, rp, bias, packed, out, steps, warmup):
     import torch
     for _ in range(warmup):
@@ -121,6 +136,8 @@ def main():
     ap.add_argument("--tile-class", type=int, default=-1)
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (reference for HBM byte counters)")
     ap.add_argument("--curve", action="store_true")
     ap.add_argument("--curve-loads", default="512,1024,2048,4096,8192")
     ap.add_argument("--curve-steps", type=int, default=20)
@@ -185,10 +202,16 @@ def main():
                    "stages_ms": stages},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel<SwiGLU> (GEMM1)", "achieved": g1,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": g1 / PEAK_BF16_TFLOPS,
-                     "traffic": None},
+                     "traffic": profiled_traffic(inp.name, "gemm1") if args.tile_class < 0 else None},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_tokens)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.curve:
         run_curve(moe, gu, packed, args)
     ctx.close()
