@@ -151,9 +151,9 @@ moe_status moe_stage_times(moe_ctx* ctx, float* ms /* host */);
  * paper's tile boundaries, Sec. 3.3.2). */
 int32_t moe_tile_rows(const moe_ctx* ctx);
 
-/* Tuning hook: force the token-tile class of the expert GEMMs (0: up to 32 rows per tile, 1: 64,
- * 2: 128, 3: 320; higher values select alternative kernels kept for tuning runs; -1: choose from
- * the expected rows per expert, the default). */
+/* Tuning hook: force the token-tile class of the expert GEMMs (0: row tiles of up to 128 rows, the
+ * low-load class; 1: up to 320 rows, the main class; higher values select alternative kernels kept
+ * for tuning runs; -1: choose from the expected rows per expert, the default). */
 moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
 
 /* Device pointers into the workspace holding the intermediates of the most recent

@@ -19,6 +19,7 @@
 #include <stdlib.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "moe_internal.h"
 
@@ -85,8 +86,9 @@ static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileD
 // p ^ swz(row).  NSTAGE-deep LDS ring, prefetch distance D = NSTAGE-1, one barrier per K step:
 //   wait own loads of stage kt | barrier | issue loads of stage kt+D into the slot read at kt-1 |
 //   MFMAs on stage kt.
-// SPREAD = 1 issues the next stage's loads in slices between the MFMA sub-steps instead of one
-// burst after the barrier.
+// SPREAD >= 1 issues the next stage's loads between the MFMAs of the first SPREAD sub-steps instead
+// of one burst after the barrier.  SWP >= 1 software-pipelines the LDS->register fragment reads one
+// MFMA sub-step ahead: explicitly scheduled reads (SWP per MFMA slot) and explicit waits.
 // Row tiles have a run-time height (a multiple of 32 rows up to BM, the last one of an expert
 // possibly ragged): 32-row blocks past the last valid row are neither loaded nor multiplied.
 // ------------------------------------------------------------------------------------------------
@@ -98,13 +100,40 @@ static __device__ inline int swz_of(int r) {
     return (CH == 8) ? ((r >> 1) & 7) : ((r >> 2) & 3);
 }
 
+// ---- explicitly scheduled LDS reads -------------------------------------------------------------
+// The compiler's own placement of ds_read / s_waitcnt leaves every MFMA group waiting for the LDS
+// reads issued just before it.  For the software-pipelined K loop the reads are issued through
+// inline asm (invisible to the compiler's wait-count pass) and waited for with exact counts:
+// the LDS returns data in order, so "lgkmcnt(N)" = everything but the N newest reads has landed.
+template <int OFF>
+static __device__ inline bf16x8_t lds_read_b128(uint32_t byte_addr) {
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(byte_addr), "n"(OFF) : "memory");
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+static __device__ inline bf16x8_t lds_read_b128_rt(uint32_t byte_addr) {
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(byte_addr) : "memory");
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+template <int STRIDE, int... I>
+static __device__ inline void lds_read_frags(bf16x8_t* f, uint32_t byte_addr, std::integer_sequence<int, I...>) {
+    ((f[I] = lds_read_b128<I * STRIDE>(byte_addr)), ...);
+}
+template <int N>
+static __device__ inline void wait_lgkmcnt() {
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+// makes the fragment "depend" on the preceding wait so that its consumers stay behind it
+static __device__ inline void tie(bf16x8_t& f) { asm volatile("" : "+v"(f)); }
+
 template <int N>
 static __device__ inline void wait_vmcnt() {
     // s_waitcnt vmcnt(N) only: expcnt = 7, lgkmcnt = 15 are left unconstrained (gfx9 encoding)
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int SPREAD, bool SWIGLU>
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int SPREAD, int SWP, bool SWIGLU>
 __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     const uint16_t* __restrict__ X, int ldx, const int32_t* __restrict__ row_map,
     const uint16_t* __restrict__ Wp, int ldw, int Np, int K, uint16_t* __restrict__ C, int ldc,
@@ -124,6 +153,7 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     static_assert(BM % (NW * RPL) == 0 && BN % (NW * RPL) == 0, "staging shape");
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4 && D * LPT < 64, "pipeline depth");
+    static_assert(TM % 16 == 0 && TN % 16 == 0 && (FM > FN ? FM : FN) * 32 * CH * 16 < 65536, "fragment addressing");
 
     extern __shared__ u32x4_t lds[];  // [NSTAGE][STAGE]: X rows then W rows
 
@@ -137,23 +167,24 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = K / BK;
 
-    // per-thread global sources (advance by BK elements per K step)
-    const uint16_t* xsrc[XPASS];
-    const uint16_t* wsrc[WPASS];
+    // per-thread global sources: 32-bit byte offsets from wave-uniform bases (the bases advance by
+    // BK elements per K step in scalar registers, the offsets never change)
+    const uint16_t* wbase = Wp + (size_t)td.expert * Np * ldw;
+    uint32_t xo[XPASS], wo[WPASS];
 #pragma unroll
     for (int p = 0; p < XPASS; ++p) {
         const int r = (p * NW + wave) * RPL + lrow;
         const int rr = r < td.rows ? r : td.rows - 1;  // clamp: rows past the end are never stored
         int grow = td.row0 + rr;
         if (row_map != nullptr) grow = row_map[grow];
-        xsrc[p] = X + (size_t)grow * ldx + (lphys ^ swz_of<CH>(r)) * 8;
+        xo[p] = (uint32_t)grow * (uint32_t)(ldx * 2) + (uint32_t)((lphys ^ swz_of<CH>(r)) * 16);
     }
 #pragma unroll
     for (int p = 0; p < WPASS; ++p) {
         const int r = (p * NW + wave) * RPL + lrow;
         int n = td.n0 + r;
         if (n >= Np) n = Np - 1;
-        wsrc[p] = Wp + ((size_t)td.expert * Np + n) * ldw + (lphys ^ swz_of<CH>(r)) * 8;
+        wo[p] = (uint32_t)n * (uint32_t)(ldw * 2) + (uint32_t)((lphys ^ swz_of<CH>(r)) * 16);
     }
     // LDS fragment addresses of this lane (in 16-byte chunks) and their XOR masks
     int xoff[FM], xswz[FM], woff[FN], wswz[FN];
@@ -168,6 +199,17 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
         const int r = wn * TN + a * 32 + frow;
         woff[a] = BM * CH + r * CH;
         wswz[a] = swz_of<CH>(r);
+    }
+
+    // byte addresses (inside a stage) of this lane's fragment chunk for every MFMA sub-step; the
+    // 32-row blocks of a wave are a constant 32*CH*16 bytes apart and share the XOR mask (the wave
+    // tile starts at a multiple of 16 rows)
+    uint32_t fx_addr[KK], fw_addr[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        const int c = kk * 2 + fhalf;
+        fx_addr[kk] = (uint32_t)((xoff[0] + (c ^ xswz[0])) * 16);
+        fw_addr[kk] = (uint32_t)((woff[0] + (c ^ wswz[0])) * 16);
     }
 
     f32x16_t acc[FN][FM];
@@ -194,14 +236,28 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
             if (q < XPASS) {
                 if ((q * NW + wave) * RPL < rows32)
                     __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(xsrc[q] + (size_t)kt * BK),
+                        (const __attribute__((address_space(1))) void*)((const char*)(X + (size_t)kt * BK) + xo[q]),
                         (__attribute__((address_space(3))) void*)(base + (q * NW + wave) * RPL * CH), 16, 0, 0);
             } else {
                 __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(wsrc[q - XPASS] + (size_t)kt * BK),
+                    (const __attribute__((address_space(1))) void*)((const char*)(wbase + (size_t)kt * BK) + wo[q - XPASS]),
                     (__attribute__((address_space(3))) void*)(base + BM * CH + ((q - XPASS) * NW + wave) * RPL * CH),
                     16, 0, 0);
             }
+        }
+    };
+    auto issue_one = [&](int kt, int q) {  // q is a compile-time constant after unrolling
+        u32x4_t* base = lds + (kt % NSTAGE) * STAGE;
+        if (q < XPASS) {
+            if ((q * NW + wave) * RPL < rows32)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)((const char*)(X + (size_t)kt * BK) + xo[q]),
+                    (__attribute__((address_space(3))) void*)(base + (q * NW + wave) * RPL * CH), 16, 0, 0);
+        } else {
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)((const char*)(wbase + (size_t)kt * BK) + wo[q - XPASS]),
+                (__attribute__((address_space(3))) void*)(base + BM * CH + ((q - XPASS) * NW + wave) * RPL * CH), 16,
+                0, 0);
         }
     };
     using IC0 = std::integral_constant<int, 0>;
@@ -233,10 +289,8 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
                 if (more) issue(kt + D, IC0{}, ICL{});
             }
             const u32x4_t* st = lds + (kt % NSTAGE) * STAGE;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const int c = kk * 2 + fhalf;
-                if constexpr (SPREAD == 1) {
+            auto spread_issue = [&](int kk) {
+                if constexpr (SPREAD >= 1) {
                     // feed the vector-memory pipe a slice of the next stage's loads per sub-step
                     // (all but the last sub-step) instead of one burst right after the barrier
                     constexpr int PH = KK > 1 ? KK - 1 : 1;
@@ -246,18 +300,75 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
                         if (kk == 2 && PH > 2) issue(kt + D, std::integral_constant<int, (LPT * 2) / PH>{}, std::integral_constant<int, (LPT * 3) / PH>{});
                     }
                 }
-                bf16x8_t wf[FN];
+            };
+            if constexpr (SWP >= 1 && FMV > 0) {
+                // fragments of sub-step kk+1 are read while the MFMAs of sub-step kk run
+                constexpr int BLK = 32 * CH * 16;  // bytes between consecutive 32-row blocks
+                using XS = std::make_integer_sequence<int, FMV>;
+                using WS = std::make_integer_sequence<int, FN>;
+                const uint32_t sbase = (uint32_t)((kt % NSTAGE) * STAGE * 16);
+                bf16x8_t xf[2][FM], wf[2][FN];
+                lds_read_frags<BLK>(xf[0], sbase + fx_addr[0], XS{});
+                lds_read_frags<BLK>(wf[0], sbase + fw_addr[0], WS{});
 #pragma unroll
-                for (int a = 0; a < FN; ++a)
-                    if (any) wf[a] = __builtin_bit_cast(bf16x8_t, st[woff[a] + (c ^ wswz[a])]);
+                for (int kk = 0; kk < KK; ++kk) {
+                    const int cur = kk & 1, nxt = cur ^ 1;
+                    // everything read for this sub-step was issued during the previous one
+                    wait_lgkmcnt<0>();
 #pragma unroll
-                for (int b = 0; b < FM; ++b)
-                    if (live(b)) {
-                        bf16x8_t xf = __builtin_bit_cast(bf16x8_t, st[xoff[b] + (c ^ xswz[b])]);
+                    for (int b = 0; b < FMV; ++b) tie(xf[cur][b]);
 #pragma unroll
-                        for (int a = 0; a < FN; ++a)
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf, acc[a][b], 0, 0, 0);
+                    for (int a = 0; a < FN; ++a) tie(wf[cur][a]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // one memory instruction after each MFMA: first the LDS reads of the next
+                    // sub-step's fragments, then this sub-step's share of the next stage's loads
+                    constexpr int NM = FMV * FN;
+                    constexpr int PHL = SPREAD < 1 ? 1 : (SPREAD > KK ? KK : SPREAD);  // sub-steps carrying loads
+                    constexpr int LPP = (LPT + PHL - 1) / PHL;                         // loads per such sub-step
+                    constexpr int RPS0 = (FMV + FN + NM - 1) / NM;
+                    constexpr int RPS = SWP > RPS0 ? SWP : RPS0;                       // LDS reads per MFMA slot
+                    constexpr int LPS = (LPP + NM - 1) / NM;                           // loads per MFMA slot
+#pragma unroll
+                    for (int m = 0; m < NM; ++m) {
+                        const int b = m / FN, a = m % FN;
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][a], xf[cur][b], acc[a][b], 0, 0, 0);
+                        if (kk + 1 < KK) {
+#pragma unroll
+                            for (int r = m * RPS; r < (m + 1) * RPS; ++r) {
+                                if (r < FN) wf[nxt][r] = lds_read_b128_rt(sbase + fw_addr[kk + 1] + r * BLK);
+                                else if (r < FN + FMV) xf[nxt][r - FN] = lds_read_b128_rt(sbase + fx_addr[kk + 1] + (r - FN) * BLK);
+                            }
+                        }
+                        if constexpr (SPREAD >= 1) {
+                            // loads of the next stage, one after each of the first MFMAs of the first
+                            // PHL sub-steps (a different issue port than the LDS reads)
+#pragma unroll
+                            for (int l = m * LPS; l < (m + 1) * LPS; ++l) {
+                                const int q = kk * LPP + l;
+                                if (kk < PHL && l < LPP && q < LPT && more) issue_one(kt + D, q);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+                }
+            } else {
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    const int c = kk * 2 + fhalf;
+                    spread_issue(kk);
+                    bf16x8_t wf[FN];
+#pragma unroll
+                    for (int a = 0; a < FN; ++a)
+                        if (any) wf[a] = __builtin_bit_cast(bf16x8_t, st[woff[a] + (c ^ wswz[a])]);
+#pragma unroll
+                    for (int b = 0; b < FM; ++b)
+                        if (live(b)) {
+                            bf16x8_t xf = __builtin_bit_cast(bf16x8_t, st[xoff[b] + (c ^ xswz[b])]);
+#pragma unroll
+                            for (int a = 0; a < FN; ++a)
+                                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[a], xf, acc[a][b], 0, 0, 0);
+                        }
+                }
             }
         }
     };
@@ -342,25 +453,26 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
 
 // ------------------------------------------------------------------------------------------------
 // Host side: tile variants, plans, launches.
-// Variant ids 0..3 are the production token-tile classes (up to 32 / 64 / 128 / 320 rows); higher ids
-// are alternatives kept for tuning runs (moe_set_tile_class).
-//   V(id, BM, BN, BK, WM, WN, NSTAGE, SPREAD)
+// Variant ids 0 and 1 are the production token-tile classes (row tiles of up to 128 rows for low
+// loads, up to 320 rows otherwise); higher ids are alternatives kept for tuning runs
+// (moe_set_tile_class).
+//   V(id, BM, BN, BK, WM, WN, NSTAGE, SPREAD, SWP)
 // ------------------------------------------------------------------------------------------------
 #define FOR_EACH_VARIANT(V)                \
-    V(0, 32, 256, 64, 1, 4, 4, 0)          \
-    V(1, 64, 256, 64, 1, 4, 3, 0)          \
-    V(2, 128, 128, 64, 2, 2, 3, 0)         \
-    V(3, 320, 256, 64, 2, 4, 2, 1)         \
-    V(4, 256, 256, 64, 2, 4, 2, 0)         \
-    V(5, 256, 256, 64, 2, 4, 2, 1)         \
-    V(6, 320, 256, 64, 2, 4, 2, 0)         \
-    V(7, 256, 128, 64, 4, 2, 3, 0)         \
-    V(8, 128, 256, 64, 2, 4, 3, 0)         \
-    V(9, 128, 256, 64, 1, 4, 3, 0)
+    V(0, 128, 256, 64, 2, 4, 3, 0, 0)      \
+    V(1, 320, 256, 64, 2, 4, 2, 3, 0)      \
+    V(2, 256, 256, 64, 2, 4, 2, 2, 1)      \
+    V(3, 320, 256, 64, 2, 4, 2, 2, 1)      \
+    V(4, 32, 256, 64, 1, 4, 4, 0, 0)       \
+    V(5, 64, 256, 64, 1, 4, 3, 0, 0)       \
+    V(6, 128, 128, 64, 2, 2, 3, 0, 0)      \
+    V(7, 256, 256, 64, 2, 4, 2, 0, 0)      \
+    V(8, 192, 256, 64, 2, 4, 2, 3, 0)      \
+    V(9, 128, 256, 64, 2, 4, 3, 2, 1)
 
 struct VariantDef { int bm, bn, bk, wm, wn, nstage; };
 static const VariantDef kVariant[GEMM_NUM_CLASSES] = {
-#define V(id, bm, bn, bk, wm, wn, ns, spread) {bm, bn, bk, wm, wn, ns},
+#define V(id, bm, bn, bk, wm, wn, ns, spread, swp) {bm, bn, bk, wm, wn, ns},
     FOR_EACH_VARIANT(V)
 #undef V
 };
@@ -368,10 +480,10 @@ static const VariantDef kVariant[GEMM_NUM_CLASSES] = {
 int gemm_class_rows(int cls) { return kVariant[cls].bm; }
 
 int gemm_pick_class(double rows_per_expert) {
-    if (rows_per_expert > 384.0) return GEMM_BM320;
-    if (rows_per_expert > 96.0) return GEMM_BM128;
-    if (rows_per_expert > 40.0) return GEMM_BM64;
-    return GEMM_BM32;
+    // Measured on the expert-parallel share (32 experts, Zipf loads): the 320-row class with balanced,
+    // block-skipping tiles wins from ~1 K rows upwards; below that the 128-row class streams the
+    // weights slightly faster (three LDS stages).
+    return rows_per_expert < 24.0 ? GEMM_LOW : GEMM_MAIN;
 }
 
 GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) {
@@ -388,16 +500,16 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) 
     return p;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NS, int SPREAD, bool SW>
+template <int BM, int BN, int BK, int WM, int WN, int NS, int SPREAD, int SWP, bool SW>
 struct Variant {
     static constexpr size_t smem = (size_t)NS * (BM + BN) * BK * 2;
     static hipError_t set_attr() {
-        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SW>,
+        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SWP, SW>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wp,
                              int ldw, int Np, int K, uint16_t* C, int ldc, const TileDesc* table, hipStream_t st) {
-        hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SW>), dim3(grid),
+        hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SWP, SW>), dim3(grid),
                            dim3(WM * WN * 64), smem, st, X, ldx, row_map, Wp, ldw, Np, K, C, ldc, table);
         return hipGetLastError();
     }
@@ -405,10 +517,10 @@ struct Variant {
 
 hipError_t gemm_init_attributes() {
     hipError_t err;
-#define V(id, bm, bn, bk, wm, wn, ns, spread)                             \
-    err = Variant<bm, bn, bk, wm, wn, ns, spread, true>::set_attr();        \
+#define V(id, bm, bn, bk, wm, wn, ns, spread, swp)                        \
+    err = Variant<bm, bn, bk, wm, wn, ns, spread, swp, true>::set_attr();        \
     if (err != hipSuccess) return err;                                    \
-    err = Variant<bm, bn, bk, wm, wn, ns, spread, false>::set_attr();       \
+    err = Variant<bm, bn, bk, wm, wn, ns, spread, swp, false>::set_attr();       \
     if (err != hipSuccess) return err;
     FOR_EACH_VARIANT(V)
 #undef V
@@ -430,9 +542,9 @@ hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int
                         const uint16_t* W13p, int d, int f, uint16_t* H, const TileDesc* table, hipStream_t st) {
     if (p.grid1 <= 0) return hipSuccess;
     switch (p.cls) {
-#define V(id, bm, bn, bk, wm, wn, ns, spread) \
+#define V(id, bm, bn, bk, wm, wn, ns, spread, swp) \
     case id:                                \
-        return Variant<bm, bn, bk, wm, wn, ns, spread, true>::launch(p.grid1, X, ldx, row_map, W13p, moe_ld_pad(d), 2 * f, d, H, moe_ld_pad(f), table, st);
+        return Variant<bm, bn, bk, wm, wn, ns, spread, swp, true>::launch(p.grid1, X, ldx, row_map, W13p, moe_ld_pad(d), 2 * f, d, H, moe_ld_pad(f), table, st);
         FOR_EACH_VARIANT(V)
 #undef V
     }
@@ -443,9 +555,9 @@ hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2
                         const TileDesc* table, hipStream_t st) {
     if (p.grid2 <= 0) return hipSuccess;
     switch (p.cls) {
-#define V(id, bm, bn, bk, wm, wn, ns, spread) \
+#define V(id, bm, bn, bk, wm, wn, ns, spread, swp) \
     case id:                                \
-        return Variant<bm, bn, bk, wm, wn, ns, spread, false>::launch(p.grid2, H, moe_ld_pad(f), nullptr, W2p, moe_ld_pad(f), d, f, Y, d, table, st);
+        return Variant<bm, bn, bk, wm, wn, ns, spread, swp, false>::launch(p.grid2, H, moe_ld_pad(f), nullptr, W2p, moe_ld_pad(f), d, f, Y, d, table, st);
         FOR_EACH_VARIANT(V)
 #undef V
     }

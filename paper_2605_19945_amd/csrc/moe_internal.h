@@ -20,7 +20,7 @@ struct TileDesc {
 };
 
 // Token-tile classes of the grouped GEMM.
-enum GemmClass { GEMM_BM32 = 0, GEMM_BM64 = 1, GEMM_BM128 = 2, GEMM_BM320 = 3, GEMM_NUM_CLASSES = 10 };
+enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_NUM_CLASSES = 10 };
 
 struct GemmPlan {
     int cls;         // GemmClass

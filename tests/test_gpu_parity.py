@@ -168,12 +168,14 @@ def ragged_offsets(rng, E_local, total, empty_frac=0.25):
 
 FFN_CASES = [
     # name, E_local, d, f, total rows, tile class
-    ("c32", 6, 128, 256, 200, 0),
-    ("c64", 6, 128, 256, 500, 1),
-    ("c128", 5, 256, 192, 900, 2),
-    ("c256", 4, 256, 320, 1500, 3),
-    ("c32_wide", 3, 320, 448, 70, 0),        # d, f not multiples of the 256-row weight tile
-    ("c256_narrow", 2, 64, 64, 700, 3),
+    ("low_small", 6, 128, 256, 200, 0),
+    ("low", 6, 128, 256, 500, 0),
+    ("main", 5, 256, 192, 900, 1),
+    ("main_big", 4, 256, 320, 1500, 1),
+    ("low_wide", 3, 320, 448, 70, 0),        # d, f not multiples of the 256-row weight tile
+    ("main_narrow", 2, 64, 64, 700, 1),
+    ("swp256", 4, 256, 320, 1500, 2),
+    ("swp320", 4, 192, 320, 1300, 3),
     ("auto", 8, 128, 256, 640, -1),
 ]
 
