@@ -21,11 +21,16 @@ bool shape_ok(const moe_shape* s) {
     if (s->e_lo < 0 || s->E_local < 1 || s->E_local > 256) return false;
     if ((int64_t)s->e_lo + s->E_local > s->E) return false;
     if (moe_rows_capacity(s, s->T_max) > (int64_t)1 << 24) return false;
+    // the GEMM kernels address their operands with 32-bit byte offsets from per-tensor bases
+    const int64_t lim = (int64_t)1 << 32;
+    if ((int64_t)s->T_max * s->d * 2 >= lim) return false;
+    if (moe_rows_capacity(s, s->T_max) * moe_ld_pad(s->f) * 2 >= lim) return false;
+    if ((int64_t)2 * s->f * moe_ld_pad(s->d) * 2 >= lim || (int64_t)s->d * moe_ld_pad(s->f) * 2 >= lim) return false;
     return true;
 }
 
 struct Layout {
-    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, H, Y, total;
+    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, table_r, logits, H, Y, total;
     int table1_cap, table2_cap;
     int64_t rows_cap;
 };
@@ -56,6 +61,17 @@ Layout make_layout(const moe_shape* s) {
     }
     L.table1 = take((size_t)L.table1_cap * sizeof(TileDesc));
     L.table2 = take((size_t)L.table2_cap * sizeof(TileDesc));
+    if (s->E >= MOE_ROUTER_GEMM_MIN_E) {
+        int cap = 0;
+        for (int v = 0; v < 4; ++v) {
+            int g = router_gemm_grid(v, s->T_max, moe_router_packed_rows(s->E));
+            if (g > cap) cap = g;
+        }
+        L.table_r = take((size_t)cap * sizeof(TileDesc));
+        L.logits = take((size_t)s->T_max * moe_router_cols(s->E) * 4);
+    } else {
+        L.table_r = L.logits = 0;
+    }
     L.H = take((size_t)L.rows_cap * moe_ld_pad(s->f) * 2);
     L.Y = take((size_t)L.rows_cap * s->d * 2);
     L.total = o;
@@ -105,6 +121,7 @@ size_t moe_workspace_bytes(const moe_shape* s) {
 
 size_t moe_packed_router_bytes(const moe_shape* s) {
     if (!shape_ok(s)) return 0;
+    if (s->E >= MOE_ROUTER_GEMM_MIN_E) return (size_t)moe_router_packed_rows(s->E) * moe_ld_pad(s->d) * 2;
     return (size_t)2 * moe_router_rows(s->E) * s->d * 2;
 }
 
@@ -135,6 +152,8 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     }
     ds = note_hip(gemm_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
     if (ds != MOE_OK) return ds;
+    ds = note_hip(router_gemm_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
+    if (ds != MOE_OK) return ds;
 
     moe_ctx* c = new (std::nothrow) moe_ctx();
     if (c == nullptr) return MOE_ERR_INVALID_ARG;
@@ -151,6 +170,8 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     c->blockhist = (int32_t*)(c->ws + L.blockhist);
     c->table1 = (TileDesc*)(c->ws + L.table1);
     c->table2 = (TileDesc*)(c->ws + L.table2);
+    c->table_r = (TileDesc*)(c->ws + L.table_r);
+    c->logits = (float*)(c->ws + L.logits);
     c->H = (uint16_t*)(c->ws + L.H);
     c->Y = (uint16_t*)(c->ws + L.Y);
     c->rows_cap = L.rows_cap;
@@ -225,7 +246,7 @@ moe_status moe_route(moe_ctx* c, const void* x, const void* rp, const float* bia
     if (bias != nullptr && !aligned(bias, 4)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     return from_hip(launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, c->s.d, c->s.E, c->s.k,
-                                 topk_idx, topk_w, counts, (hipStream_t)stream));
+                                 topk_idx, topk_w, counts, c->logits, c->table_r, (hipStream_t)stream));
 }
 
 moe_status moe_permute(moe_ctx* c, const void* x, const int32_t* topk_idx, int32_t T, void* xp,
@@ -295,7 +316,7 @@ moe_status moe_layer_forward(moe_ctx* c, const void* x, const void* rp, const fl
 
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_ROUTE], st);
     hipError_t e = launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, s.d, s.E, s.k, c->idx, c->w,
-                                counts, st);
+                                counts, c->logits, c->table_r, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_PERMUTE], st);
     e = launch_permute(c->idx, T, s.k, s.e_lo, s.E_local, c->blockhist, c->offsets, c->row_of, c->tok_of, st);

@@ -31,10 +31,12 @@ static __device__ inline uint32_t pack2_bf16(float a, float b) {
 }
 static __device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
 
+enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_PAIR_SUM_F32 = 2 };
+
 // Epilogue shared by the GEMM kernels.  Accumulator element v of lane l in block (a, b) is
 //   weight row  a*32 + 8*(v/4) + 4*(l/32) + v%4,   token row  b*32 + l%32,
 // so a lane owns 4 consecutive output columns of one token row per accumulator quad.
-template <int FM, int FN, int TM, int TN, bool SWIGLU>
+template <int FM, int FN, int TM, int TN, int EPI>
 static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileDesc& td, int Np,
                                             uint16_t* __restrict__ C, int ldc, int wm, int wn, int lane) {
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -43,7 +45,24 @@ static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileD
         const int trow = wm * TM + b * 32 + frow;
         if (trow >= td.rows) continue;
         uint16_t* crow = C + (size_t)(td.row0 + trow) * ldc;
-        if constexpr (SWIGLU) {
+        if constexpr (EPI == EPI_PAIR_SUM_F32) {
+            // router logits: the even block holds the products with the high bf16 term of Wg, the odd
+            // block those with the low term; their sum is stored as fp32 (C is a float matrix)
+            float* frow_out = (float*)C + (size_t)(td.row0 + trow) * ldc;
+#pragma unroll
+            for (int a2 = 0; a2 < FN / 2; ++a2) {
+                const int prow = td.n0 + wn * TN + a2 * 64;
+                if (prow >= Np) continue;
+                const int col = prow / 2 + 4 * fhalf;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4_t o;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) o[v] = acc[2 * a2][b][4 * q + v] + acc[2 * a2 + 1][b][4 * q + v];
+                    *(f32x4_t*)(frow_out + col + 8 * q) = o;
+                }
+            }
+        } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
             for (int a2 = 0; a2 < FN / 2; ++a2) {
                 const int prow = td.n0 + wn * TN + a2 * 64;  // packed row of the gate block
@@ -133,7 +152,7 @@ static __device__ inline void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int SPREAD, int SWP, bool SWIGLU>
+template <int BM, int BN, int BK, int WM, int WN, int NSTAGE, int SPREAD, int SWP, int EPI>
 __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     const uint16_t* __restrict__ X, int ldx, const int32_t* __restrict__ row_map,
     const uint16_t* __restrict__ Wp, int ldw, int Np, int K, uint16_t* __restrict__ C, int ldc,
@@ -149,7 +168,7 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     constexpr int D = NSTAGE - 1;
     constexpr int KK = BK / 16;                // MFMA sub-steps per K step
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be made of 32x32 blocks");
-    static_assert(!SWIGLU || FN % 2 == 0, "SwiGLU needs gate/up block pairs in one wave");
+    static_assert(EPI == EPI_PLAIN || FN % 2 == 0, "paired epilogues need both blocks of a pair in one wave");
     static_assert(BM % (NW * RPL) == 0 && BN % (NW * RPL) == 0, "staging shape");
     static_assert(BK == 32 || BK == 64, "BK");
     static_assert(NSTAGE >= 2 && NSTAGE <= 4 && D * LPT < 64, "pipeline depth");
@@ -376,32 +395,39 @@ __global__ __launch_bounds__(WM* WN * 64) void grouped_gemm_kernel(
     else if (FM > 1 && fm_valid == FM - 1) main_loop(std::integral_constant<int, (FM > 1 ? FM - 1 : 0)>{});
     else main_loop(std::integral_constant<int, -1>{});
 
-    gemm_epilogue<FM, FN, TM, TN, SWIGLU>(acc, td, Np, C, ldc, wm, wn, lane);
+    gemm_epilogue<FM, FN, TM, TN, EPI>(acc, td, Np, C, ldc, wm, wn, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Device-side work list.  The rows of expert e are cut into ceil(n_e / bm) row tiles of nearly
 // equal height (a multiple of 32 rows, at most bm): an expert slightly larger than a multiple of
 // the tile height does not get a nearly empty extra tile, its rows are spread over taller tiles.
-// Work-item id b runs on XCD b % 8 (workgroups are dealt round-robin to the 8 XCDs); XCD x owns the
-// weight-row tiles x, x+8, ...; inside an XCD the order is expert-major, then weight-row tile, then
-// row tile (fastest), so the ~32 workgroups resident on an XCD cover all row tiles of one expert
-// times a handful of its weight tiles and share both through that XCD's L2.
+// The list order is expert-major, then weight-row tile, then row tile (fastest); chunks of 4
+// consecutive items (row tiles sharing a weight panel) are dealt round-robin to the 8 XCDs, so the
+// workgroups resident on one XCD reuse weight panels in that XCD's L2 and every XCD gets the same
+// amount of work whatever the number of weight-row tiles.
 // ------------------------------------------------------------------------------------------------
+constexpr int SCHED_CHUNK = 4;
+static inline int sched_grid(int mt_max, int nt) {
+    const int chunks = (mt_max * nt + SCHED_CHUNK - 1) / SCHED_CHUNK;
+    return 8 * SCHED_CHUNK * ((chunks + 7) / 8);
+}
+
 __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict__ offsets, int E_local,
                                                        int bm, int bn, int nt1, int grid1,
                                                        TileDesc* __restrict__ t1, int nt2, int grid2,
-                                                       TileDesc* __restrict__ t2) {
+                                                       TileDesc* __restrict__ t2, int host_rows) {
     __shared__ int32_t pre[257];  // exclusive prefix of row tiles per expert; pre[E_local] = total
     __shared__ int32_t off[257];
     __shared__ int32_t scan[256];
     const int tid = threadIdx.x;
     int mt = 0;
+    // host_rows >= 0: one group of host_rows rows (the router GEMM), no offsets array to read
     if (tid < E_local) {
-        int n = offsets[tid + 1] - offsets[tid];
+        int n = host_rows >= 0 ? host_rows : offsets[tid + 1] - offsets[tid];
         mt = (n + bm - 1) / bm;
     }
-    for (int i = tid; i <= E_local; i += 256) off[i] = offsets[i];
+    for (int i = tid; i <= E_local; i += 256) off[i] = host_rows >= 0 ? i * host_rows : offsets[i];
     scan[tid] = mt;
     __syncthreads();
     for (int o = 1; o < 256; o <<= 1) {
@@ -420,21 +446,24 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
         const int grid = which ? grid2 : grid1;
         TileDesc* table = which ? t2 : t1;
         for (int b = blockIdx.x * 256 + tid; b < grid; b += gridDim.x * 256) {
-            const int x = b & 7, j = b >> 3;
-            const int cnt = nt > x ? (nt - x + 7) / 8 : 0;  // weight-row tiles owned by XCD x
+            // XCD-aware order: the linear list (expert-major, then weight-row tile, then row tile) is
+            // cut into chunks of SCHED_CHUNK consecutive items -- row tiles that share one weight
+            // panel -- and the chunks are dealt round-robin to the 8 XCDs (work item b runs on XCD b % 8)
+            const int x = b & 7, slot = b >> 3;
+            const int L = ((slot / SCHED_CHUNK) * 8 + x) * SCHED_CHUNK + slot % SCHED_CHUNK;
             TileDesc td;
             td.expert = 0; td.row0 = 0; td.rows = 0; td.n0 = 0;
-            if (j < MT * cnt) {
-                // largest e with pre[e] * cnt <= j  (that expert has at least one row tile)
+            if (L < MT * nt) {
+                // largest e with pre[e] * nt <= L  (that expert has at least one row tile)
                 int lo = 0, hi = E_local;
                 while (hi - lo > 1) {
                     int mid = (lo + hi) >> 1;
-                    if (pre[mid] * cnt <= j) lo = mid; else hi = mid;
+                    if (pre[mid] * nt <= L) lo = mid; else hi = mid;
                 }
                 const int e = lo;
                 const int mte = pre[e + 1] - pre[e];
-                const int r = j - pre[e] * cnt;
-                const int mi = r % mte, nl = r / mte;
+                const int r = L - pre[e] * nt;
+                const int mi = r % mte, ni = r / mte;
                 const int e_rows = off[e + 1] - off[e];
                 // 32-row blocks of the expert, dealt evenly to its mte tiles
                 const int nblk = (e_rows + 31) / 32;
@@ -444,7 +473,7 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                 td.expert = e;
                 td.row0 = off[e] + blk0 * 32;
                 td.rows = min(nb * 32, e_rows - blk0 * 32);
-                td.n0 = (nl * 8 + x) * bn;
+                td.n0 = ni * bn;
             }
             table[b] = td;
         }
@@ -495,21 +524,21 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) 
     p.mt_max = (int)(n_rows_cap / p.bm + extra);
     p.nt1 = (2 * f + p.bn - 1) / p.bn;
     p.nt2 = (d + p.bn - 1) / p.bn;
-    p.grid1 = 8 * p.mt_max * ((p.nt1 + 7) / 8);
-    p.grid2 = 8 * p.mt_max * ((p.nt2 + 7) / 8);
+    p.grid1 = sched_grid(p.mt_max, p.nt1);
+    p.grid2 = sched_grid(p.mt_max, p.nt2);
     return p;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NS, int SPREAD, int SWP, bool SW>
+template <int BM, int BN, int BK, int WM, int WN, int NS, int SPREAD, int SWP, int EPI>
 struct Variant {
     static constexpr size_t smem = (size_t)NS * (BM + BN) * BK * 2;
     static hipError_t set_attr() {
-        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SWP, SW>,
+        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SWP, EPI>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wp,
                              int ldw, int Np, int K, uint16_t* C, int ldc, const TileDesc* table, hipStream_t st) {
-        hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SWP, SW>), dim3(grid),
+        hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, WM, WN, NS, SPREAD, SWP, EPI>), dim3(grid),
                            dim3(WM * WN * 64), smem, st, X, ldx, row_map, Wp, ldw, Np, K, C, ldc, table);
         return hipGetLastError();
     }
@@ -518,9 +547,9 @@ struct Variant {
 hipError_t gemm_init_attributes() {
     hipError_t err;
 #define V(id, bm, bn, bk, wm, wn, ns, spread, swp)                        \
-    err = Variant<bm, bn, bk, wm, wn, ns, spread, swp, true>::set_attr();        \
+    err = Variant<bm, bn, bk, wm, wn, ns, spread, swp, EPI_SWIGLU>::set_attr();        \
     if (err != hipSuccess) return err;                                    \
-    err = Variant<bm, bn, bk, wm, wn, ns, spread, swp, false>::set_attr();       \
+    err = Variant<bm, bn, bk, wm, wn, ns, spread, swp, EPI_PLAIN>::set_attr();       \
     if (err != hipSuccess) return err;
     FOR_EACH_VARIANT(V)
 #undef V
@@ -534,7 +563,7 @@ hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_loca
     if (blocks < 1) blocks = 1;
     if (blocks > 64) blocks = 64;
     hipLaunchKernelGGL(schedule_kernel, dim3(blocks), dim3(256), 0, st, offsets, E_local, p.bm, p.bn, p.nt1,
-                       p.grid1, t1, p.nt2, p.grid2, t2);
+                       p.grid1, t1, p.nt2, p.grid2, t2, -1);
     return hipGetLastError();
 }
 
@@ -544,7 +573,7 @@ hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int
     switch (p.cls) {
 #define V(id, bm, bn, bk, wm, wn, ns, spread, swp) \
     case id:                                \
-        return Variant<bm, bn, bk, wm, wn, ns, spread, swp, true>::launch(p.grid1, X, ldx, row_map, W13p, moe_ld_pad(d), 2 * f, d, H, moe_ld_pad(f), table, st);
+        return Variant<bm, bn, bk, wm, wn, ns, spread, swp, EPI_SWIGLU>::launch(p.grid1, X, ldx, row_map, W13p, moe_ld_pad(d), 2 * f, d, H, moe_ld_pad(f), table, st);
         FOR_EACH_VARIANT(V)
 #undef V
     }
@@ -557,8 +586,61 @@ hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2
     switch (p.cls) {
 #define V(id, bm, bn, bk, wm, wn, ns, spread, swp) \
     case id:                                \
-        return Variant<bm, bn, bk, wm, wn, ns, spread, swp, false>::launch(p.grid2, H, moe_ld_pad(f), nullptr, W2p, moe_ld_pad(f), d, f, Y, d, table, st);
+        return Variant<bm, bn, bk, wm, wn, ns, spread, swp, EPI_PLAIN>::launch(p.grid2, H, moe_ld_pad(f), nullptr, W2p, moe_ld_pad(f), d, f, Y, d, table, st);
         FOR_EACH_VARIANT(V)
+#undef V
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---- router logits as a one-group GEMM (E >= 32): logits[T, Ep] = x[T, d] * Wg, fp32 ------------
+// Router rows are packed like W1|W3: 32-row blocks alternate between the high and the low bf16 term
+// of the same 32 experts, and the epilogue adds the two accumulators.
+#define FOR_EACH_ROUTER_VARIANT(V)  \
+    V(0, 32, 256, 64, 1, 4, 4, 0)   \
+    V(1, 64, 256, 64, 1, 4, 3, 0)   \
+    V(2, 128, 256, 64, 2, 4, 3, 0)  \
+    V(3, 320, 256, 64, 2, 4, 2, 3)
+
+static const int kRouterBm[4] = {32, 64, 128, 320};
+
+hipError_t router_gemm_init_attributes() {
+    hipError_t err;
+#define V(id, bm, bn, bk, wm, wn, ns, spread)                                   \
+    err = Variant<bm, bn, bk, wm, wn, ns, spread, 0, EPI_PAIR_SUM_F32>::set_attr(); \
+    if (err != hipSuccess) return err;
+    FOR_EACH_ROUTER_VARIANT(V)
+#undef V
+    return hipSuccess;
+}
+
+int router_gemm_pick(int T, int Rp) {
+    // smallest row tile that still gives every CU a work item
+    const int nt = (Rp + 255) / 256;
+    for (int v = 3; v > 0; --v)
+        if ((T / kRouterBm[v]) * nt >= 256) return v;
+    return 0;
+}
+
+int router_gemm_grid(int v, int T_max, int Rp) {
+    const int nt = (Rp + 255) / 256;
+    return sched_grid(T_max / kRouterBm[v] + 1, nt);
+}
+
+hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
+                              TileDesc* table, hipStream_t st) {
+    const int v = router_gemm_pick(T, Rp);
+    const int nt = (Rp + 255) / 256;
+    const int grid = router_gemm_grid(v, T, Rp);
+    hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
+                       kRouterBm[v], 256, nt, grid, table, 0, 0, (TileDesc*)nullptr, T);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    switch (v) {
+#define V(id, bm, bn, bk, wm, wn, ns, spread) \
+    case id:                                  \
+        return Variant<bm, bn, bk, wm, wn, ns, spread, 0, EPI_PAIR_SUM_F32>::launch(grid, x, d, nullptr, rp, moe_ld_pad(d), Rp, d, (uint16_t*)logits, ldl, table, st);
+        FOR_EACH_ROUTER_VARIANT(V)
 #undef V
     }
     return hipErrorInvalidValue;

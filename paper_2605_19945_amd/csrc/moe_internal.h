@@ -47,6 +47,8 @@ struct moe_ctx {
     int32_t* blockhist;  // [nblk_max, E_local]
     TileDesc* table1;    // [grid1_max]
     TileDesc* table2;    // [grid2_max]
+    TileDesc* table_r;   // router GEMM work list (E >= MOE_ROUTER_GEMM_MIN_E)
+    float* logits;       // [T_max, router cols] fp32 (E >= MOE_ROUTER_GEMM_MIN_E)
     uint16_t* H;         // [rows_cap, f] bf16
     uint16_t* Y;         // [rows_cap, d] bf16
     int64_t rows_cap;
@@ -62,6 +64,11 @@ static inline int64_t moe_round_up(int64_t a, int64_t b) { return (a + b - 1) / 
 // weights, the intermediate H): rows are padded by 128 bytes so that the rows of a tile, which
 // are all read at the same K offset, do not fall on one L2 channel when K*2 is a power of two.
 static __host__ __device__ inline int moe_ld_pad(int K) { return K + 64; }
+// Routers with at least this many experts compute their logits with the tiled GEMM kernel; smaller
+// ones with the direct MFMA kernel.
+constexpr int MOE_ROUTER_GEMM_MIN_E = 32;
+static inline int moe_router_cols(int E) { return (E + 31) / 32 * 32; }       // logits row length (GEMM path)
+static inline int moe_router_packed_rows(int E) { return moe_router_cols(E) * 2; }  // hi/lo interleaved rows
 static inline int moe_router_rows(int E) {  // packed router rows: multiple of 16, power-of-two blocks
     int nb = (E + 15) / 16;
     int p = 1;
@@ -74,7 +81,8 @@ hipError_t launch_pack_router(const float* Wg, int d, int E, uint16_t* rp, hipSt
 hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uint16_t* W2, int E_local,
                                int d, int f, uint16_t* packed, hipStream_t st);
 hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias, int T, int d, int E,
-                        int k, int32_t* idx, float* w, int32_t* counts, hipStream_t st);
+                        int k, int32_t* idx, float* w, int32_t* counts, float* logits_ws, TileDesc* table_ws,
+                        hipStream_t st);
 hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
                           int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st);
 hipError_t launch_gather(const uint16_t* x, const int32_t* tok_of, const int32_t* offsets, int E_local,
@@ -86,6 +94,10 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f);
 int gemm_pick_class(double expected_rows_per_expert);
 int gemm_class_rows(int cls);
 hipError_t gemm_init_attributes();
+hipError_t router_gemm_init_attributes();
+int router_gemm_grid(int variant, int T_max, int Rp);
+hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
+                              TileDesc* table, hipStream_t st);
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,
                            TileDesc* t2, hipStream_t st);
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,

@@ -31,7 +31,32 @@ __global__ void pack_router_kernel(const float* __restrict__ Wg, int d, int E, i
     }
 }
 
+// GEMM-path layout (E >= MOE_ROUTER_GEMM_MIN_E): rows [(e/32)*64 + s*32 + e%32][ld(d)], s = 0 high
+// term, s = 1 low term, experts padded to a multiple of 32 with zero rows, rows padded like the
+// expert weights.
+__global__ void pack_router_gemm_kernel(const float* __restrict__ Wg, int d, int E, int Ep, int ld,
+                                        uint16_t* __restrict__ rp) {
+    size_t n = (size_t)Ep * d;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < n; o += (size_t)gridDim.x * blockDim.x) {
+        int e = (int)(o / d), i = (int)(o % d);
+        float v = e < E ? Wg[(size_t)i * E + e] : 0.f;
+        uint16_t hi = f32_to_bf16_rne(v);
+        uint16_t lo = f32_to_bf16_rne(v - bf16_to_f32(hi));
+        size_t row = (size_t)(e / 32) * 64 + (e % 32);
+        rp[row * ld + i] = hi;
+        rp[(row + 32) * ld + i] = lo;
+    }
+}
+
 hipError_t launch_pack_router(const float* Wg, int d, int E, uint16_t* rp, hipStream_t st) {
+    if (E >= MOE_ROUTER_GEMM_MIN_E) {
+        int Ep = moe_router_cols(E);
+        size_t n = (size_t)Ep * d;
+        int blocks = (int)((n + 255) / 256);
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(pack_router_gemm_kernel, dim3(blocks), dim3(256), 0, st, Wg, d, E, Ep, moe_ld_pad(d), rp);
+        return hipGetLastError();
+    }
     int R = moe_router_rows(E);
     size_t n = (size_t)R * d;
     int blocks = (int)((n + 255) / 256);
@@ -89,7 +114,7 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(const uint16_t* __restri
     const uint16_t* hrow = rp + (size_t)(lane & 15) * d + 8 * (lane >> 4);
     const uint16_t* lrow = rp_lo + (size_t)(lane & 15) * d + 8 * (lane >> 4);
 
-#pragma unroll 4
+#pragma unroll 8
     for (int s = s_begin; s < s_end; ++s) {
         bf16x8_t xf = __builtin_bit_cast(bf16x8_t, *(const uint4*)(xrow + s * 32));
 #pragma unroll
@@ -170,6 +195,70 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(const uint16_t* __restri
         if (hist[e] != 0) atomicAdd(&counts[e], hist[e]);
 }
 
+// Top-k / softmax / counts from fp32 logits in global memory (the GEMM router path): one wavefront
+// per token, same key construction and tie-break as route_kernel.
+template <int EPL>
+__global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ logits, int ldl,
+                                                   const float* __restrict__ bias, int T, int E, int k,
+                                                   int32_t* __restrict__ idx, float* __restrict__ w,
+                                                   int32_t* __restrict__ counts) {
+    __shared__ int32_t hist[64 * EPL];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int e = tid; e < 64 * EPL; e += 256) hist[e] = 0;
+    __syncthreads();
+    const int tokens_per_block = 16;
+    for (int i = wave; i < tokens_per_block; i += 4) {
+        const int t = blockIdx.x * tokens_per_block + i;
+        if (t >= T) break;
+        unsigned long long key[EPL];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+            int e = lane + 64 * j;
+            key[j] = 0ull;
+            if (e < E) {
+                float v = logits[(size_t)t * ldl + e];
+                if (bias != nullptr) v += bias[e];
+                key[j] = ((unsigned long long)float_order_bits(v) << 32) |
+                         (unsigned long long)(0xFFFFFFFFu - (uint32_t)e);
+            }
+        }
+        float my_val = 0.f;
+        int my_e = 0;
+        for (int j = 0; j < k; ++j) {
+            unsigned long long best = key[0];
+#pragma unroll
+            for (int q = 1; q < EPL; ++q) best = key[q] > best ? key[q] : best;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                unsigned long long o = __shfl_xor(best, off, 64);
+                best = o > best ? o : best;
+            }
+            uint32_t e_sel = 0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull);
+#pragma unroll
+            for (int q = 0; q < EPL; ++q)
+                if ((int)e_sel == lane + 64 * q) key[q] = 0ull;
+            if (lane == j) {
+                my_e = (int)e_sel;
+                my_val = float_from_order_bits((uint32_t)(best >> 32));
+            }
+        }
+        float l0 = __shfl(my_val, 0, 64);
+        float ex = lane < k ? expf(my_val - l0) : 0.f;
+        float sum = ex;
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if (lane < k) {
+            size_t o = (size_t)t * k + lane;
+            idx[o] = my_e;
+            w[o] = ex / sum;
+            atomicAdd(&hist[my_e], 1);
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += 256)
+        if (hist[e] != 0) atomicAdd(&counts[e], hist[e]);
+}
+
 __global__ void zero_i32_kernel(int32_t* p, int n) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
@@ -187,13 +276,26 @@ static hipError_t route_launch_t(const uint16_t* x, const uint16_t* rp, const fl
 }
 
 hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias, int T, int d, int E, int k,
-                        int32_t* idx, float* w, int32_t* counts, hipStream_t st) {
+                        int32_t* idx, float* w, int32_t* counts, float* logits_ws, TileDesc* table_ws,
+                        hipStream_t st) {
     hipLaunchKernelGGL(zero_i32_kernel, dim3((E + 255) / 256), dim3(256), 0, st, counts, E);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
+    if (E >= MOE_ROUTER_GEMM_MIN_E) {
+        // logits on the tiled GEMM kernel (reduction over d, two bf16 terms of Wg), then top-k
+        const int Ep = moe_router_cols(E);
+        err = launch_router_gemm(x, rp, T, d, 2 * Ep, logits_ws, Ep, table_ws, st);
+        if (err != hipSuccess) return err;
+        const int blocks = (T + 15) / 16;
+        const int epl = (E + 63) / 64;
+        if (epl <= 1) hipLaunchKernelGGL(topk_kernel<1>, dim3(blocks), dim3(256), 0, st, logits_ws, Ep, bias, T, E, k, idx, w, counts);
+        else if (epl == 2) hipLaunchKernelGGL(topk_kernel<2>, dim3(blocks), dim3(256), 0, st, logits_ws, Ep, bias, T, E, k, idx, w, counts);
+        else hipLaunchKernelGGL(topk_kernel<4>, dim3(blocks), dim3(256), 0, st, logits_ws, Ep, bias, T, E, k, idx, w, counts);
+        return hipGetLastError();
+    }
     int nb = moe_router_rows(E) / 16;
     switch (nb) {
-        case 1: return route_launch_t<1, 8>(x, rp, bias, T, d, E, k, idx, w, counts, st);
+        case 1: return route_launch_t<1, 16>(x, rp, bias, T, d, E, k, idx, w, counts, st);
         case 2: return route_launch_t<2, 8>(x, rp, bias, T, d, E, k, idx, w, counts, st);
         case 4: return route_launch_t<4, 4>(x, rp, bias, T, d, E, k, idx, w, counts, st);
         case 8: return route_launch_t<8, 4>(x, rp, bias, T, d, E, k, idx, w, counts, st);
