@@ -54,7 +54,7 @@ Layout make_layout(const moe_shape* s) {
     const int nblk = (s->T_max + 255) / 256;
     L.blockhist = take((size_t)nblk * s->E_local * 4);
     L.table1_cap = L.table2_cap = 0;
-    for (int c = 0; c < GEMM_NUM_CLASSES; ++c) {
+    for (int c = 0; c < GEMM_ALL_CLASSES; ++c) {
         GemmPlan p = gemm_make_plan(c, L.rows_cap, s->E_local, s->d, s->f);
         if (p.grid1 > L.table1_cap) L.table1_cap = p.grid1;
         if (p.grid2 > L.table2_cap) L.table2_cap = p.grid2;
@@ -127,7 +127,7 @@ size_t moe_packed_router_bytes(const moe_shape* s) {
 
 size_t moe_packed_weight_bytes(const moe_shape* s) {
     if (!shape_ok(s)) return 0;
-    return (size_t)s->E_local * ((size_t)2 * s->f * moe_ld_pad(s->d) + (size_t)s->d * moe_ld_pad(s->f)) * 2;
+    return (moe_packed_rowmajor_elems(s->E_local, s->d, s->f) + (size_t)s->E_local * 3 * s->d * s->f) * 2;
 }
 
 moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t bytes) {
@@ -153,6 +153,7 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     ds = note_hip(gemm_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
     if (ds != MOE_OK) return ds;
     ds = note_hip(router_gemm_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
+    if (ds == MOE_OK) ds = note_hip(gemm_dw_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
     if (ds != MOE_OK) return ds;
 
     moe_ctx* c = new (std::nothrow) moe_ctx();
@@ -212,7 +213,7 @@ void moe_destroy(moe_ctx* c) {
 }
 
 moe_status moe_set_tile_class(moe_ctx* c, int32_t cls) {
-    if (c == nullptr || cls < -1 || cls >= GEMM_NUM_CLASSES) return MOE_ERR_INVALID_ARG;
+    if (c == nullptr || cls < -1 || cls >= GEMM_ALL_CLASSES) return MOE_ERR_INVALID_ARG;
     c->forced_cls = cls;
     return MOE_OK;
 }
@@ -276,10 +277,15 @@ static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t*
     hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM1], st);
-    e = launch_gemm1(p, X, s.d, row_map, w13p, s.d, s.f, c->H, c->table1, st);
+    const bool dw = cls >= GEMM_NUM_CLASSES;
+    const uint16_t* w13f = packed + moe_packed_rowmajor_elems(s.E_local, s.d, s.f);
+    const uint16_t* w2f = w13f + (size_t)s.E_local * 2 * s.f * s.d;
+    e = dw ? launch_gemm1_dw(cls - GEMM_NUM_CLASSES, p.grid1, X, s.d, row_map, w13f, s.d, s.f, c->H, c->table1, st)
+           : launch_gemm1(p, X, s.d, row_map, w13p, s.d, s.f, c->H, c->table1, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM2], st);
-    e = launch_gemm2(p, c->H, w2p, s.d, s.f, Y, c->table2, st);
+    e = dw ? launch_gemm2_dw(cls - GEMM_NUM_CLASSES, p.grid2, c->H, w2f, s.d, s.f, Y, c->table2, st)
+           : launch_gemm2(p, c->H, w2p, s.d, s.f, Y, c->table2, st);
     return from_hip(e);
 }
 

@@ -20,7 +20,10 @@ struct TileDesc {
 };
 
 // Token-tile classes of the grouped GEMM.
-enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_NUM_CLASSES = 10 };
+enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_NUM_CLASSES = 11 };
+// Direct-weight classes follow the LDS-staged ones: class GEMM_NUM_CLASSES + i.
+constexpr int GEMM_DW_CLASSES = 4;
+constexpr int GEMM_ALL_CLASSES = GEMM_NUM_CLASSES + GEMM_DW_CLASSES;
 
 struct GemmPlan {
     int cls;         // GemmClass
@@ -64,6 +67,10 @@ static inline int64_t moe_round_up(int64_t a, int64_t b) { return (a + b - 1) / 
 // weights, the intermediate H): rows are padded by 128 bytes so that the rows of a tile, which
 // are all read at the same K offset, do not fall on one L2 channel when K*2 is a power of two.
 static __host__ __device__ inline int moe_ld_pad(int K) { return K + 64; }
+// elements of the row-major packed weights (W13p then W2p); the fragment-major copies follow them
+static inline size_t moe_packed_rowmajor_elems(int E_local, int d, int f) {
+    return (size_t)E_local * ((size_t)2 * f * moe_ld_pad(d) + (size_t)d * moe_ld_pad(f));
+}
 // Routers with at least this many experts compute their logits with the tiled GEMM kernel; smaller
 // ones with the direct MFMA kernel.
 constexpr int MOE_ROUTER_GEMM_MIN_E = 32;
@@ -103,5 +110,12 @@ hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_loca
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13p, int d, int f, uint16_t* H, const TileDesc* table,
                         hipStream_t st);
+int gemm_dw_class_rows(int i);
+hipError_t gemm_dw_init_attributes();
+hipError_t launch_gemm1_dw(int i, int grid, const uint16_t* X, int ldx, const int32_t* row_map,
+                           const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table,
+                           hipStream_t st);
+hipError_t launch_gemm2_dw(int i, int grid, const uint16_t* H, const uint16_t* W2f, int d, int f, uint16_t* Y,
+                           const TileDesc* table, hipStream_t st);
 hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2p, int d, int f,
                         uint16_t* Y, const TileDesc* table, hipStream_t st);

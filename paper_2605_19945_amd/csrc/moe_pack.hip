@@ -31,6 +31,37 @@ __global__ __launch_bounds__(256) void transpose_pack_kernel(const uint16_t* __r
     }
 }
 
+// Fragment-major packing for the direct-weight GEMM: in [K][C] (per expert, K = reduction index)
+//   out[e][nb][k / 16][l][j] = in[e][16*(k/16) + 8*(l/32) + j][c],   c = cb*32 + l % 32,
+// where nb = cb (plain) or 2*cb + slot (gate/up interleave: even row blocks W1, odd row blocks W3).
+__global__ __launch_bounds__(256) void fragment_pack_kernel(const uint16_t* __restrict__ in, int K, int C,
+                                                            uint16_t* __restrict__ out, int n_blocks /* per expert */,
+                                                            int interleave, int slot) {
+    __shared__ uint16_t tile[64][66];  // [k][c]
+    const int e = blockIdx.z;
+    const int c0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const uint16_t* src = in + (size_t)e * K * C;
+    for (int kk = ty; kk < 64; kk += 4) tile[kk][tx] = src[(size_t)(k0 + kk) * C + c0 + tx];
+    __syncthreads();
+    // 2 column blocks x 4 K chunks = 8 fragments of 64 lanes x 8 elements
+    for (int frag = ty; frag < 8; frag += 4) {
+        const int cb = frag >> 2, kc = frag & 3, l = tx;
+        const int nb_plain = c0 / 32 + cb;
+        const int nb = interleave ? 2 * nb_plain + slot : nb_plain;
+        uint16_t* dst = out + (((size_t)e * n_blocks + nb) * (K / 16) + (k0 / 16 + kc)) * 512 + l * 8;
+        uint16_t v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = tile[kc * 16 + 8 * (l >> 5) + j][cb * 32 + (l & 31)];
+        u32x4_t o;
+        o.x = v[0] | ((uint32_t)v[1] << 16);
+        o.y = v[2] | ((uint32_t)v[3] << 16);
+        o.z = v[4] | ((uint32_t)v[5] << 16);
+        o.w = v[6] | ((uint32_t)v[7] << 16);
+        *(u32x4_t*)dst = o;
+    }
+}
+
 hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uint16_t* W2, int E_local, int d,
                                int f, uint16_t* packed, hipStream_t st) {
     uint16_t* w13p = packed;
@@ -39,5 +70,11 @@ hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uin
     hipLaunchKernelGGL(transpose_pack_kernel, g13, dim3(256), 0, st, W1, d, f, w13p, 2 * f, 1, 0);
     hipLaunchKernelGGL(transpose_pack_kernel, g13, dim3(256), 0, st, W3, d, f, w13p, 2 * f, 1, 1);
     hipLaunchKernelGGL(transpose_pack_kernel, g2, dim3(256), 0, st, W2, f, d, w2p, d, 0, 0);
+    // fragment-major copies (direct-weight GEMM classes)
+    uint16_t* w13f = packed + moe_packed_rowmajor_elems(E_local, d, f);
+    uint16_t* w2f = w13f + (size_t)E_local * 2 * f * d;
+    hipLaunchKernelGGL(fragment_pack_kernel, g13, dim3(256), 0, st, W1, d, f, w13f, 2 * f / 32, 1, 0);
+    hipLaunchKernelGGL(fragment_pack_kernel, g13, dim3(256), 0, st, W3, d, f, w13f, 2 * f / 32, 1, 1);
+    hipLaunchKernelGGL(fragment_pack_kernel, g2, dim3(256), 0, st, W2, f, d, w2f, d / 32, 0, 0);
     return hipGetLastError();
 }
