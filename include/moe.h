@@ -79,14 +79,15 @@ int64_t moe_rows_capacity(const moe_shape* shape /* host */, int32_t T);
 /* ---- one-off, at model-load time (the analogue of loading each expert's weights onto its
  * assigned GPU, paper Sec. 3.3.4); not part of the layer latency ------------------------------ */
 
-/* Router matrix Wg [d, E] fp32 row-major -> opaque packed form (two bf16 terms per weight,
- * transposed so the reduction dimension is contiguous). */
+/* Router matrix Wg [d, E] fp32 row-major -> opaque packed form (two bf16 terms per weight, laid
+ * out in the order the matrix-core operand fragments are loaded). */
 size_t moe_packed_router_bytes(const moe_shape* shape /* host */);
 moe_status moe_pack_router(moe_ctx* ctx, const float* Wg, void* router_packed, void* stream);
 
 /* Expert weights W1, W3 [E_local, d, f] and W2 [E_local, f, d], bf16 row-major -> opaque packed
- * form (transposed so the reduction dimension is contiguous; W1 and W3 interleaved in blocks of
- * 32 output columns so one accumulator tile holds both branches of the SwiGLU). */
+ * form (3 * E_local * d * f bf16 values: every 32-column x 16-reduction-element block stored as the
+ * 1 KB matrix-core operand fragment one wavefront loads; W1 and W3 interleaved in blocks of 32
+ * output columns so one accumulator tile holds both branches of the SwiGLU). */
 size_t moe_packed_weight_bytes(const moe_shape* shape /* host */);
 moe_status moe_pack_weights(moe_ctx* ctx, const void* W1, const void* W3, const void* W2,
                             void* packed, void* stream);
@@ -147,12 +148,12 @@ moe_status moe_stage_times(moe_ctx* ctx, float* ms /* host */);
 
 /* Largest token-tile height of the expert GEMMs for this shape.  An expert's rows are cut into
  * ceil(n / height) tiles of nearly equal height (multiples of 32 rows); the work per tile grows in
- * steps of 32 rows per wavefront row, which sets the staircase of the latency-vs-load curve (the
+ * steps of 32 rows, which sets the staircase of the latency-vs-load curve (the
  * paper's tile boundaries, Sec. 3.3.2). */
 int32_t moe_tile_rows(const moe_ctx* ctx);
 
 /* Tuning hook: force the token-tile class of the expert GEMMs (0: row tiles of up to 128 rows, the
- * low-load class; 1: up to 320 rows, the main class; higher values select alternative kernels kept
+ * low-load class; 1: up to 256 rows, the main class; higher values select alternative kernels kept
  * for tuning runs; -1: choose from the expected rows per expert, the default). */
 moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
 

@@ -21,11 +21,11 @@ bool shape_ok(const moe_shape* s) {
     if (s->e_lo < 0 || s->E_local < 1 || s->E_local > 256) return false;
     if ((int64_t)s->e_lo + s->E_local > s->E) return false;
     if (moe_rows_capacity(s, s->T_max) > (int64_t)1 << 24) return false;
-    // the GEMM kernels address their operands with 32-bit byte offsets from per-tensor bases
+    // the GEMM kernels address their token operands with 32-bit byte offsets from per-tensor bases
     const int64_t lim = (int64_t)1 << 32;
     if ((int64_t)s->T_max * s->d * 2 >= lim) return false;
     if (moe_rows_capacity(s, s->T_max) * moe_ld_pad(s->f) * 2 >= lim) return false;
-    if ((int64_t)2 * s->f * moe_ld_pad(s->d) * 2 >= lim || (int64_t)s->d * moe_ld_pad(s->f) * 2 >= lim) return false;
+    if (moe_rows_capacity(s, s->T_max) * s->d * 2 >= lim) return false;
     return true;
 }
 
@@ -54,7 +54,7 @@ Layout make_layout(const moe_shape* s) {
     const int nblk = (s->T_max + 255) / 256;
     L.blockhist = take((size_t)nblk * s->E_local * 4);
     L.table1_cap = L.table2_cap = 0;
-    for (int c = 0; c < GEMM_ALL_CLASSES; ++c) {
+    for (int c = 0; c < GEMM_NUM_CLASSES; ++c) {
         GemmPlan p = gemm_make_plan(c, L.rows_cap, s->E_local, s->d, s->f);
         if (p.grid1 > L.table1_cap) L.table1_cap = p.grid1;
         if (p.grid2 > L.table2_cap) L.table2_cap = p.grid2;
@@ -62,11 +62,7 @@ Layout make_layout(const moe_shape* s) {
     L.table1 = take((size_t)L.table1_cap * sizeof(TileDesc));
     L.table2 = take((size_t)L.table2_cap * sizeof(TileDesc));
     if (s->E >= MOE_ROUTER_GEMM_MIN_E) {
-        int cap = 0;
-        for (int v = 0; v < 4; ++v) {
-            int g = router_gemm_grid(v, s->T_max, moe_router_packed_rows(s->E));
-            if (g > cap) cap = g;
-        }
+        const int cap = router_gemm_grid_max(s->T_max, moe_router_packed_rows(s->E));
         L.table_r = take((size_t)cap * sizeof(TileDesc));
         L.logits = take((size_t)s->T_max * moe_router_cols(s->E) * 4);
     } else {
@@ -121,13 +117,13 @@ size_t moe_workspace_bytes(const moe_shape* s) {
 
 size_t moe_packed_router_bytes(const moe_shape* s) {
     if (!shape_ok(s)) return 0;
-    if (s->E >= MOE_ROUTER_GEMM_MIN_E) return (size_t)moe_router_packed_rows(s->E) * moe_ld_pad(s->d) * 2;
+    if (s->E >= MOE_ROUTER_GEMM_MIN_E) return (size_t)moe_router_packed_rows(s->E) * s->d * 2;
     return (size_t)2 * moe_router_rows(s->E) * s->d * 2;
 }
 
 size_t moe_packed_weight_bytes(const moe_shape* s) {
     if (!shape_ok(s)) return 0;
-    return (moe_packed_rowmajor_elems(s->E_local, s->d, s->f) + (size_t)s->E_local * 3 * s->d * s->f) * 2;
+    return (size_t)s->E_local * 3 * s->d * s->f * 2;
 }
 
 moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t bytes) {
@@ -151,9 +147,6 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
         return MOE_ERR_DEVICE;
     }
     ds = note_hip(gemm_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
-    if (ds != MOE_OK) return ds;
-    ds = note_hip(router_gemm_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
-    if (ds == MOE_OK) ds = note_hip(gemm_dw_init_attributes(), "hipFuncSetAttribute(max dynamic LDS)");
     if (ds != MOE_OK) return ds;
 
     moe_ctx* c = new (std::nothrow) moe_ctx();
@@ -213,7 +206,7 @@ void moe_destroy(moe_ctx* c) {
 }
 
 moe_status moe_set_tile_class(moe_ctx* c, int32_t cls) {
-    if (c == nullptr || cls < -1 || cls >= GEMM_ALL_CLASSES) return MOE_ERR_INVALID_ARG;
+    if (c == nullptr || cls < -1 || cls >= GEMM_NUM_CLASSES) return MOE_ERR_INVALID_ARG;
     c->forced_cls = cls;
     return MOE_OK;
 }
@@ -272,20 +265,15 @@ static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t*
     GemmPlan p = gemm_make_plan(cls, n_rows_cap, s.E_local, s.d, s.f);
     if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
     c->last_cls = cls;
-    const uint16_t* w13p = packed;
-    const uint16_t* w2p = packed + (size_t)s.E_local * 2 * s.f * moe_ld_pad(s.d);
+    const uint16_t* w13f = packed;
+    const uint16_t* w2f = packed + (size_t)s.E_local * 2 * s.f * s.d;
     hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM1], st);
-    const bool dw = cls >= GEMM_NUM_CLASSES;
-    const uint16_t* w13f = packed + moe_packed_rowmajor_elems(s.E_local, s.d, s.f);
-    const uint16_t* w2f = w13f + (size_t)s.E_local * 2 * s.f * s.d;
-    e = dw ? launch_gemm1_dw(cls - GEMM_NUM_CLASSES, p.grid1, X, s.d, row_map, w13f, s.d, s.f, c->H, c->table1, st)
-           : launch_gemm1(p, X, s.d, row_map, w13p, s.d, s.f, c->H, c->table1, st);
+    e = launch_gemm1(p, X, s.d, row_map, w13f, s.d, s.f, c->H, c->table1, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM2], st);
-    e = dw ? launch_gemm2_dw(cls - GEMM_NUM_CLASSES, p.grid2, c->H, w2f, s.d, s.f, Y, c->table2, st)
-           : launch_gemm2(p, c->H, w2p, s.d, s.f, Y, c->table2, st);
+    e = launch_gemm2(p, c->H, w2f, s.d, s.f, Y, c->table2, st);
     return from_hip(e);
 }
 

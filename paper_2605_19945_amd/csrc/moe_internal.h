@@ -20,10 +20,7 @@ struct TileDesc {
 };
 
 // Token-tile classes of the grouped GEMM.
-enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_NUM_CLASSES = 11 };
-// Direct-weight classes follow the LDS-staged ones: class GEMM_NUM_CLASSES + i.
-constexpr int GEMM_DW_CLASSES = 4;
-constexpr int GEMM_ALL_CLASSES = GEMM_NUM_CLASSES + GEMM_DW_CLASSES;
+enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_NUM_CLASSES = 4 };
 
 struct GemmPlan {
     int cls;         // GemmClass
@@ -63,14 +60,10 @@ struct moe_ctx {
 };
 
 static inline int64_t moe_round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
-// Leading dimension (elements) of a K-contiguous operand the library lays out itself (packed
-// weights, the intermediate H): rows are padded by 128 bytes so that the rows of a tile, which
-// are all read at the same K offset, do not fall on one L2 channel when K*2 is a power of two.
+// Leading dimension (elements) of the intermediate H, which the library lays out itself: rows are
+// padded by 128 bytes so that the rows of a tile, which are all read at the same K offset, do not
+// fall on one L2 channel when K*2 is a power of two.
 static __host__ __device__ inline int moe_ld_pad(int K) { return K + 64; }
-// elements of the row-major packed weights (W13p then W2p); the fragment-major copies follow them
-static inline size_t moe_packed_rowmajor_elems(int E_local, int d, int f) {
-    return (size_t)E_local * ((size_t)2 * f * moe_ld_pad(d) + (size_t)d * moe_ld_pad(f));
-}
 // Routers with at least this many experts compute their logits with the tiled GEMM kernel; smaller
 // ones with the direct MFMA kernel.
 constexpr int MOE_ROUTER_GEMM_MIN_E = 32;
@@ -101,21 +94,13 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f);
 int gemm_pick_class(double expected_rows_per_expert);
 int gemm_class_rows(int cls);
 hipError_t gemm_init_attributes();
-hipError_t router_gemm_init_attributes();
-int router_gemm_grid(int variant, int T_max, int Rp);
+int router_gemm_grid_max(int T_max, int Rp);
 hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
                               TileDesc* table, hipStream_t st);
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,
                            TileDesc* t2, hipStream_t st);
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
-                        const uint16_t* W13p, int d, int f, uint16_t* H, const TileDesc* table,
+                        const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table,
                         hipStream_t st);
-int gemm_dw_class_rows(int i);
-hipError_t gemm_dw_init_attributes();
-hipError_t launch_gemm1_dw(int i, int grid, const uint16_t* X, int ldx, const int32_t* row_map,
-                           const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table,
-                           hipStream_t st);
-hipError_t launch_gemm2_dw(int i, int grid, const uint16_t* H, const uint16_t* W2f, int d, int f, uint16_t* Y,
-                           const TileDesc* table, hipStream_t st);
-hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2p, int d, int f,
+hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2f, int d, int f,
                         uint16_t* Y, const TileDesc* table, hipStream_t st);

@@ -1,37 +1,16 @@
 // Load-time repacking of the expert weights (the analogue of the paper's deployment step, which
 // places each expert's weights on its GPU once, Sec. 3.3.4).  Not on the hot path.
 //
-// Packed layout (bf16): [ W13p : E_local x 2f x ld(d) ][ W2p : E_local x d x ld(f) ], ld(K) = K + 64
-// (rows padded by 128 bytes, see moe_ld_pad)
-//   W13p[e][(c/32)*64 + s*32 + c%32][i] = (s == 0 ? W1 : W3)[e][i][c]     (c < f, i < d)
-//   W2p [e][c][j]                       = W2[e][j][c]                     (c < d, j < f)
-// i.e. every matrix is transposed so that the reduction dimension is contiguous, and W1/W3 are
-// interleaved in blocks of 32 output columns so that one 32x32 accumulator pair of the first GEMM
-// holds the gate and the up projection of the same (row, column).
+// Packed layout (bf16), MFMA-fragment order: [ W13f : E_local x 2f/32 x d/16 x 64 x 8 ]
+//                                            [ W2f  : E_local x d/32  x f/16 x 64 x 8 ]
+//   Wf[e][nb][kc][l][j] = (packed weight row 32*nb + l%32, reduction element 16*kc + 8*(l/32) + j)
+// where packed row n of W13 is column c = 32*(n/64) + n%32 of W1 (n%64 < 32) or of W3 (n%64 >= 32)
+// -- gate and up projection interleaved in blocks of 32 columns, so that one 32x32 accumulator pair
+// of the first GEMM holds both for the same (row, column) -- and packed row c of W2f is column c of
+// W2.  One (nb, kc) fragment is the 1 KB a wavefront loads for one MFMA operand.
 #include "moe_internal.h"
 
-// in [R][C] (per expert) -> out[map(c)][R]; R, C multiples of 64.
-__global__ __launch_bounds__(256) void transpose_pack_kernel(const uint16_t* __restrict__ in, int R, int C,
-                                                             uint16_t* __restrict__ out,
-                                                             int out_rows /* rows per expert in out */,
-                                                             int interleave, int slot) {
-    __shared__ uint16_t tile[64][66];
-    const int e = blockIdx.z;
-    const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const uint16_t* src = in + (size_t)e * R * C;
-    const int ld = moe_ld_pad(R);
-    uint16_t* dst = out + (size_t)e * out_rows * ld;
-    for (int rr = ty; rr < 64; rr += 4) tile[rr][tx] = src[(size_t)(r0 + rr) * C + c0 + tx];
-    __syncthreads();
-    for (int cc = ty; cc < 64; cc += 4) {
-        int c = c0 + cc;
-        int orow = interleave ? (c / 32) * 64 + slot * 32 + (c % 32) : c;
-        dst[(size_t)orow * ld + r0 + tx] = tile[tx][cc];
-    }
-}
-
-// Fragment-major packing for the direct-weight GEMM: in [K][C] (per expert, K = reduction index)
+// in [K][C] (per expert, K = reduction index) ->
 //   out[e][nb][k / 16][l][j] = in[e][16*(k/16) + 8*(l/32) + j][c],   c = cb*32 + l % 32,
 // where nb = cb (plain) or 2*cb + slot (gate/up interleave: even row blocks W1, odd row blocks W3).
 __global__ __launch_bounds__(256) void fragment_pack_kernel(const uint16_t* __restrict__ in, int K, int C,
@@ -64,15 +43,9 @@ __global__ __launch_bounds__(256) void fragment_pack_kernel(const uint16_t* __re
 
 hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uint16_t* W2, int E_local, int d,
                                int f, uint16_t* packed, hipStream_t st) {
-    uint16_t* w13p = packed;
-    uint16_t* w2p = packed + (size_t)E_local * 2 * f * moe_ld_pad(d);
+    uint16_t* w13f = packed;
+    uint16_t* w2f = packed + (size_t)E_local * 2 * f * d;
     dim3 g13(f / 64, d / 64, E_local), g2(d / 64, f / 64, E_local);
-    hipLaunchKernelGGL(transpose_pack_kernel, g13, dim3(256), 0, st, W1, d, f, w13p, 2 * f, 1, 0);
-    hipLaunchKernelGGL(transpose_pack_kernel, g13, dim3(256), 0, st, W3, d, f, w13p, 2 * f, 1, 1);
-    hipLaunchKernelGGL(transpose_pack_kernel, g2, dim3(256), 0, st, W2, f, d, w2p, d, 0, 0);
-    // fragment-major copies (direct-weight GEMM classes)
-    uint16_t* w13f = packed + moe_packed_rowmajor_elems(E_local, d, f);
-    uint16_t* w2f = w13f + (size_t)E_local * 2 * f * d;
     hipLaunchKernelGGL(fragment_pack_kernel, g13, dim3(256), 0, st, W1, d, f, w13f, 2 * f / 32, 1, 0);
     hipLaunchKernelGGL(fragment_pack_kernel, g13, dim3(256), 0, st, W3, d, f, w13f, 2 * f / 32, 1, 1);
     hipLaunchKernelGGL(fragment_pack_kernel, g2, dim3(256), 0, st, W2, f, d, w2f, d / 32, 0, 0);

@@ -31,30 +31,41 @@ __global__ void pack_router_kernel(const float* __restrict__ Wg, int d, int E, i
     }
 }
 
-// GEMM-path layout (E >= MOE_ROUTER_GEMM_MIN_E): rows [(e/32)*64 + s*32 + e%32][ld(d)], s = 0 high
-// term, s = 1 low term, experts padded to a multiple of 32 with zero rows, rows padded like the
-// expert weights.
-__global__ void pack_router_gemm_kernel(const float* __restrict__ Wg, int d, int E, int Ep, int ld,
+// GEMM-path layout (E >= MOE_ROUTER_GEMM_MIN_E), MFMA-fragment order like the expert weights:
+//   rp[nb][kc][l][j] = term (nb % 2) of Wg[16*kc + 8*(l/32) + j][32*(nb/2) + l%32]
+// (term 0 = high bf16 part, term 1 = low part; experts padded to a multiple of 32 with zeros).
+__global__ void pack_router_gemm_kernel(const float* __restrict__ Wg, int d, int E, int Ep,
                                         uint16_t* __restrict__ rp) {
-    size_t n = (size_t)Ep * d;
+    const size_t n = (size_t)(2 * Ep / 32) * (d / 16) * 64;  // 16-byte chunks
     for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < n; o += (size_t)gridDim.x * blockDim.x) {
-        int e = (int)(o / d), i = (int)(o % d);
-        float v = e < E ? Wg[(size_t)i * E + e] : 0.f;
-        uint16_t hi = f32_to_bf16_rne(v);
-        uint16_t lo = f32_to_bf16_rne(v - bf16_to_f32(hi));
-        size_t row = (size_t)(e / 32) * 64 + (e % 32);
-        rp[row * ld + i] = hi;
-        rp[(row + 32) * ld + i] = lo;
+        const int l = (int)(o % 64);
+        const int kc = (int)((o / 64) % (d / 16));
+        const int nb = (int)(o / 64 / (d / 16));
+        const int e = 32 * (nb / 2) + (l & 31), term = nb & 1;
+        uint16_t v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = 16 * kc + 8 * (l >> 5) + j;
+            const float x = e < E ? Wg[(size_t)i * E + e] : 0.f;
+            const uint16_t hi = f32_to_bf16_rne(x);
+            v[j] = term == 0 ? hi : f32_to_bf16_rne(x - bf16_to_f32(hi));
+        }
+        u32x4_t q;
+        q.x = v[0] | ((uint32_t)v[1] << 16);
+        q.y = v[2] | ((uint32_t)v[3] << 16);
+        q.z = v[4] | ((uint32_t)v[5] << 16);
+        q.w = v[6] | ((uint32_t)v[7] << 16);
+        *(u32x4_t*)(rp + o * 8) = q;
     }
 }
 
 hipError_t launch_pack_router(const float* Wg, int d, int E, uint16_t* rp, hipStream_t st) {
     if (E >= MOE_ROUTER_GEMM_MIN_E) {
         int Ep = moe_router_cols(E);
-        size_t n = (size_t)Ep * d;
+        size_t n = (size_t)Ep * d / 4;
         int blocks = (int)((n + 255) / 256);
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(pack_router_gemm_kernel, dim3(blocks), dim3(256), 0, st, Wg, d, E, Ep, moe_ld_pad(d), rp);
+        hipLaunchKernelGGL(pack_router_gemm_kernel, dim3(blocks), dim3(256), 0, st, Wg, d, E, Ep, rp);
         return hipGetLastError();
     }
     int R = moe_router_rows(E);

@@ -214,7 +214,7 @@ def test_grouped_ffn_all_rows_in_one_expert_and_rows_cap_larger_than_used(moe):
     xp = wl.gaussian_bf16_bits(8, 9, (cap, d), 1.0)
     ctx = moe.MoEContext(cap, d, f, E_local, 1)
     packed = ctx.moe_pack_weights(gu.to_dev_bf16(W1), gu.to_dev_bf16(W3), gu.to_dev_bf16(W2))
-    for cls in range(15):
+    for cls in range(4):
         ctx.moe_set_tile_class(cls)
         y = torch.full((cap, d), 7.0, dtype=torch.bfloat16, device="cuda")
         ctx.moe_grouped_ffn(gu.to_dev_bf16(xp), gu.to_dev(off), cap, packed, y=y)
@@ -290,7 +290,7 @@ def test_layer_parity(moe, case):
     ctx.close()
 
 
-@pytest.mark.parametrize("cls", list(range(15)))
+@pytest.mark.parametrize("cls", list(range(4)))
 def test_layer_parity_every_tile_class(moe, cls):
     print(f"layer tile class {cls}", flush=True)
     inp = wl.custom("cls", 700, 128, 256, 8, 2, seed=cls, wg_std=0.08, w_std=0.06)
