@@ -1,404 +1,33 @@
-// Grouped expert GEMMs on the gfx950 matrix cores -- the paper's "isolated MoE expert kernel"
-// (Sec. 3.3.2), whose latency over token count is the staircase GEM samples at tile boundaries.
-//
-//   GEMM1 + SwiGLU:  H[r, c] = silu(sum_i X[r,i] W1[e][i,c]) * (sum_i X[r,i] W3[e][i,c])
-//   GEMM2:           Y[r, c] = sum_j H[r,j] W2[e][j,c]
-// for the rows r of expert e (ragged, device-side counts), bf16 operands, fp32 accumulation.
-// The router logits of large routers (E >= 32) run on the same kernel as one group.
-//
-// Design (CDNA4):
-//   * work item = up to BM rows of ONE expert x 256 packed weight rows; the list of work items is
-//     built on the device from the per-expert offsets (no host sync), experts with no rows get
-//     none, row tiles have a run-time height (a multiple of 32 rows, the last one of an expert
-//     possibly ragged: loads clamped, stores masked) -- no padding to the largest expert.
-//   * v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the first operand and the TOKEN rows as the
-//     second, so a lane's accumulator holds 4 consecutive output columns of one token row.
-//   * only the token rows go through LDS.  The weights are stored at load time in MFMA-fragment
-//     order
-//        Wf[e][n / 32][k / 16][lane][8],  lane l <-> packed weight row 32*(n/32) + l % 32,
-//                                         reduction elements 16*(k/16) + 8*(l/32) .. +8,
-//     so a wavefront fetches one 32x16 operand fragment with ONE fully coalesced 1 KB load straight
-//     into the registers the MFMA reads, two K steps ahead of its use (three register buffers).
-//     The token rows are staged by global_load_lds into an NSX-deep LDS ring (XOR-swizzled 16-byte
-//     chunks, see swz_of) and every wavefront multiplies ALL rows of the tile by its own 64 weight
-//     rows (1 x 4 wave layout): no weight byte is loaded twice or touches LDS, and the LDS ring is
-//     deep because it only holds the tokens (NSX-1 token stages and two weight stages, about
-//     150 KB per compute unit, are in flight towards L2).
-//   * one wavefront per SIMD (256 threads, up to 512 registers per lane, accumulators in AGPRs),
-//     so all latency hiding is explicit: LDS fragment reads run one MFMA sub-step ahead, the
-//     barrier that publishes stage kt+1 sits before the LAST sub-step of stage kt so that the first
-//     fragments of the next stage are read under those MFMAs, and the loads of a K step are spread
-//     one by one over its MFMA slots (bursts from four lockstep wavefronts overrun the compute
-//     unit's single vector-memory pipe and stall MFMA issue).
-//   * work items are ordered so that the workgroups running concurrently on one XCD share weight
-//     panels through that XCD's L2.
+// Work list, tile classes, plans and launches of the grouped GEMMs (the kernel itself lives in
+// moe_gemm_kernel.h and is instantiated per epilogue in moe_gemm_{swiglu,plain,pairsum}.hip).
 #include <stdlib.h>
-
-#include <type_traits>
-#include <utility>
 
 #include "moe_internal.h"
 
-static __device__ inline uint32_t pack2_bf16(float a, float b) {
-    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-    ua += 0x7FFFu + ((ua >> 16) & 1u);
-    ub += 0x7FFFu + ((ub >> 16) & 1u);
-    return (ua >> 16) | (ub & 0xFFFF0000u);
-}
-static __device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
-
-enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_PAIR_SUM_F32 = 2 };
-
-// Epilogues.  Accumulator element v of lane l in block (a, b) is
-//   weight row  a*32 + 8*(v/4) + 4*(l/32) + v%4,   token row  b*32 + l%32,
-// so a lane owns 4 consecutive output columns of one token row per accumulator quad.
-template <int FM, int FN, int TM, int TN, int EPI>
-static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileDesc& td, int Np,
-                                            uint16_t* __restrict__ C, int ldc, int wm, int wn, int lane) {
-    const int frow = lane & 31, fhalf = lane >> 5;
-#pragma unroll
-    for (int b = 0; b < FM; ++b) {
-        const int trow = wm * TM + b * 32 + frow;
-        if (trow >= td.rows) continue;
-        uint16_t* crow = C + (size_t)(td.row0 + trow) * ldc;
-        if constexpr (EPI == EPI_PAIR_SUM_F32) {
-            // router logits: the even block holds the products with the high bf16 term of Wg, the odd
-            // block those with the low term; their sum is stored as fp32 (C is a float matrix)
-            float* frow_out = (float*)C + (size_t)(td.row0 + trow) * ldc;
-#pragma unroll
-            for (int a2 = 0; a2 < FN / 2; ++a2) {
-                const int prow = td.n0 + wn * TN + a2 * 64;
-                if (prow >= Np) continue;
-                const int col = prow / 2 + 4 * fhalf;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4_t o;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) o[v] = acc[2 * a2][b][4 * q + v] + acc[2 * a2 + 1][b][4 * q + v];
-                    *(f32x4_t*)(frow_out + col + 8 * q) = o;
-                }
-            }
-        } else if constexpr (EPI == EPI_SWIGLU) {
-#pragma unroll
-            for (int a2 = 0; a2 < FN / 2; ++a2) {
-                const int prow = td.n0 + wn * TN + a2 * 64;  // packed row of the gate block
-                if (prow >= Np) continue;
-                const int hcol = prow / 2 + 4 * fhalf;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float h[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        h[v] = silu_f32(acc[2 * a2][b][4 * q + v]) * acc[2 * a2 + 1][b][4 * q + v];
-                    u32x2_t o;
-                    o.x = pack2_bf16(h[0], h[1]);
-                    o.y = pack2_bf16(h[2], h[3]);
-                    *(u32x2_t*)(crow + hcol + 8 * q) = o;
-                }
-            }
-        } else {
-#pragma unroll
-            for (int a = 0; a < FN; ++a) {
-                const int col = td.n0 + wn * TN + a * 32;
-                if (col >= Np) continue;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    u32x2_t o;
-                    o.x = pack2_bf16(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]);
-                    o.y = pack2_bf16(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                    *(u32x2_t*)(crow + col + 4 * fhalf + 8 * q) = o;
-                }
-            }
-        }
-    }
-}
-
-template <int CH>
-static __device__ inline int swz_of(int r) {
-    // LDS: 64 banks x 4 B; a ds_read_b128 is served 16 lanes (256 B) per cycle.  The 16 rows a
-    // lane group reads at one logical chunk must land in 16 distinct 16-byte slots of a 256-byte
-    // bank line: rows sharing a bank-line position (r mod (16/CH)) get distinct XOR masks.
-    static_assert(CH == 8, "128-byte staged rows");
-    return (r >> 1) & 7;
-}
-
-// ---- explicitly scheduled LDS reads -------------------------------------------------------------
-// The compiler's own placement of ds_read / s_waitcnt leaves every MFMA group waiting for the LDS
-// reads issued just before it.  The reads of the software-pipelined K loop are issued through
-// inline asm (invisible to the compiler's wait-count pass) and waited for explicitly.
-template <int OFF>
-static __device__ inline bf16x8_t lds_read_b128(uint32_t byte_addr) {
-    u32x4_t v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(byte_addr), "n"(OFF) : "memory");
-    return __builtin_bit_cast(bf16x8_t, v);
-}
-template <int N>
-static __device__ inline void wait_lgkmcnt() {
-    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
-}
-// makes the fragment "depend" on the preceding wait so that its consumers stay behind it
-static __device__ inline void tie(bf16x8_t& f) { asm volatile("" : "+v"(f)); }
-
-template <int N>
-static __device__ inline void wait_vmcnt() {
-    // s_waitcnt vmcnt(N) only: expcnt = 7, lgkmcnt = 15 are left unconstrained (gfx9 encoding)
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 0xF) | ((N >> 4) << 14));
-}
-
-
-template <int... I, class F>
-static __device__ inline void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, class F>
-static __device__ inline void static_for(F&& f) {
-    static_for_impl(std::make_integer_sequence<int, N>{}, f);
-}
-
-// s_waitcnt vmcnt(n) for a wave-uniform run-time n (the instruction takes an immediate)
-static __device__ inline void wait_vmcnt_rt(int n) {
-    switch (n) {
-#define C(i) case i: wait_vmcnt<i>(); break;
-        C(1) C(2) C(3) C(4) C(5) C(6) C(7) C(8) C(9) C(10) C(11) C(12) C(13) C(14) C(15) C(16) C(17) C(18)
-        C(19) C(20) C(21) C(22) C(23) C(24) C(25) C(26) C(27) C(28) C(29) C(30) C(31) C(32)
-#undef C
-        default: wait_vmcnt<0>(); break;
-    }
-}
-
-template <int BM, int NSX, int EPI>
-__global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
-                                                      const int32_t* __restrict__ row_map,
-                                                      const uint16_t* __restrict__ Wf, int Np, int K,
-                                                      uint16_t* __restrict__ C, int ldc,
-                                                      const TileDesc* __restrict__ table) {
-    constexpr int BN = 256, BK = 64, NW = 4, TN = BN / NW, FN = TN / 32, FM = BM / 32;
-    constexpr int CH = BK / 8;   // 16-byte chunks per staged token row
-    constexpr int RPL = 64 / CH; // rows covered by one wave-level load
-    constexpr int KK = BK / 16;  // MFMA sub-steps per K step
-    constexpr int DX = NSX - 1;  // token prefetch distance (K steps)
-    constexpr int WPF = 2;       // weight prefetch distance (K steps); WPF + 1 register buffers
-    constexpr int WL = FN * KK;  // weight loads per lane per K step
-    constexpr int STAGE = BM * CH;            // 16-byte chunks per token stage
-    constexpr int BLK = 32 * CH * 16;         // bytes between consecutive 32-row blocks in a stage
-    static_assert(FN == 2 && KK == 4, "wave tile");
-    static_assert(BM % 32 == 0 && FM >= 1 && FM <= 8, "row tile");
-    static_assert(NSX >= 3 && (2 * FM + WL) <= 32, "pipeline depth");
-
-    extern __shared__ u32x4_t lds[];  // [NSX][STAGE]
-
-    const TileDesc td = table[blockIdx.x];
-    if (td.rows <= 0) return;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lrow = lane / CH, lphys = lane % CH;
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int KT = K / BK;
-    const int fmv = (td.rows + 31) / 32;  // valid 32-row blocks: the same for all four wavefronts
-
-    // token sources: pass p of a wavefront brings rows 32*p + 8*wave .. +8 of the tile (one pass per
-    // 32-row block), 32-bit byte offsets from the wave-uniform base X + kt*BK
-    uint32_t xo[FM];
-#pragma unroll
-    for (int p = 0; p < FM; ++p) {
-        const int r = (p * NW + wave) * RPL + lrow;
-        const int rr = r < td.rows ? r : td.rows - 1;  // clamp: rows past the end are never stored
-        int grow = td.row0 + rr;
-        if (row_map != nullptr) grow = row_map[grow];
-        xo[p] = (uint32_t)grow * (uint32_t)(ldx * 2) + (uint32_t)((lphys ^ swz_of<CH>(r)) * 16);
-    }
-    // weight sources: fragment (row block nb, K chunk kc) is the 1 KB at ((e*Np/32 + nb)*K/16 + kc)*1 KB;
-    // wave-uniform bases (scalar registers) plus the lane's 16 bytes
-    const int nbt = Np / 32;
-    const char* wsrc[FN];
-#pragma unroll
-    for (int a = 0; a < FN; ++a) {
-        int nb = (td.n0 + wave * TN) / 32 + a;
-        if (nb >= nbt) nb = nbt - 1;  // past the last weight row: computed, never stored
-        wsrc[a] = (const char*)(Wf + ((size_t)td.expert * nbt + nb) * ((size_t)K * 32));
-    }
-    const uint32_t wlane = (uint32_t)lane * 16u;
-    // LDS byte address (inside a stage) of this lane's chunk of block 0 for every MFMA sub-step
-    uint32_t fx_addr[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-        fx_addr[kk] = (uint32_t)((frow * CH + ((kk * 2 + fhalf) ^ swz_of<CH>(frow))) * 16);
-
-    f32x16_t acc[FN][FM];
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-        for (int b = 0; b < FM; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
-    auto main_loop = [&](auto fmv_c) {
-        constexpr int FMV = decltype(fmv_c)::value;  // valid 32-row blocks (compile time)
-        constexpr int NM = FMV * FN;                 // MFMAs per sub-step
-        constexpr int NL = WL + FMV;                 // loads per lane per K step
-
-        bf16x8_t wr[WPF + 1][KK][FN];
-        bf16x8_t xf[2][FMV];
-
-        auto issue_x_one = [&](int kt, int p) {
-            u32x4_t* base = lds + (kt % NSX) * STAGE;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)((const char*)(X + (size_t)kt * BK) + xo[p]),
-                (__attribute__((address_space(3))) void*)(base + (p * NW + wave) * RPL * CH), 16, 0, 0);
-        };
-        // Weight loads go through inline asm: the compiler's own wait-count pass would otherwise put a
-        // nearly-zero vmcnt in front of the MFMAs that consume them (it cannot see through the
-        // unrolled, branched loop) and collapse the prefetch distance.  They are waited for together
-        // with the token loads, with exact counts, before the barrier that precedes their use.
-        auto load_w_one = [&](int kt, auto buf_c, auto j_c) {  // j = kk * FN + a
-            constexpr int BUF = decltype(buf_c)::value;
-            constexpr int kk = decltype(j_c)::value / FN, a = decltype(j_c)::value % FN;
-            u32x4_t v;
-            const char* base = wsrc[a] + (size_t)kt * (KK * 1024);
-            asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"
-                         : "=v"(v)
-                         : "v"(wlane), "s"(base), "n"(kk * 1024)
-                         : "memory");
-            wr[BUF][kk][a] = __builtin_bit_cast(bf16x8_t, v);
-        };
-        // prologue: weights of stages 0, 1 and tokens of stages 0 .. DX-1, oldest needs first
-        static_for<WL>([&](auto j) { load_w_one(0, std::integral_constant<int, 0>{}, j); });
-        static_for<FMV>([&](auto p) { issue_x_one(0, p); });
-        int after0 = 0;  // loads issued after those of stage 0
-        if (1 < KT) {
-            static_for<WL>([&](auto j) { load_w_one(1, std::integral_constant<int, 1>{}, j); });
-            after0 += WL;
-        }
-#pragma unroll
-        for (int s = 1; s < DX; ++s)
-            if (s < KT) {
-                static_for<FMV>([&](auto p) { issue_x_one(s, p); });
-                after0 += FMV;
-            }
-        wait_vmcnt_rt(after0);
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        static_for<FMV>([&](auto b) { xf[0][b] = lds_read_b128<b * BLK>(fx_addr[0]); });
-
-        // one K step; BUF = kt % (WPF + 1) is a compile-time register-buffer index.  STEADY: the step
-        // is neither among the first nor the last ones, so every prefetch of it exists and nothing
-        // in it is conditional.
-        auto step = [&](int kt, auto buf_c, auto steady_c) {
-            constexpr int BUF = decltype(buf_c)::value;
-            constexpr bool STEADY = decltype(steady_c)::value;
-            constexpr int NBUF = (BUF + WPF) % (WPF + 1);  // buffer of stage kt + WPF
-            const bool more_w = STEADY || kt + WPF < KT;
-            const bool more_x = STEADY || kt + DX < KT;
-            const bool next = STEADY || kt + 1 < KT;
-            const uint32_t sbase = (uint32_t)((kt % NSX) * STAGE * 16);
-            const uint32_t nbase = (uint32_t)(((kt + 1) % NSX) * STAGE * 16);
-            // the weights of this stage landed before the barrier that published it
-            static_for<WL>([&](auto j) { tie(wr[BUF][decltype(j)::value / FN][decltype(j)::value % FN]); });
-            static_for<KK>([&](auto kk_c) {
-                constexpr int kk = decltype(kk_c)::value;
-                constexpr int cur = kk & 1, nxt = cur ^ 1;
-                if constexpr (kk == KK - 1) {
-                    // publish stage kt+1 before the last sub-step: own loads of stage kt+1 have landed
-                    // (what may stay in flight: the tokens issued one step ago, after the weights of
-                    // stage kt+1, and everything issued during this step), all wavefronts have issued
-                    // and completed every LDS read of stage kt
-                    if constexpr (STEADY) {
-                        wait_vmcnt<WL + 2 * FMV>();
-                    } else {
-                        int pending = (more_w ? WL : 0) + (more_x ? FMV : 0);
-                        if (kt >= 1) {
-                            pending += kt - 1 + DX < KT ? FMV : 0;
-                        } else {
-#pragma unroll
-                            for (int s = 2; s < DX; ++s) pending += s < KT ? FMV : 0;  // issued by the prologue
-                        }
-                        if (next) wait_vmcnt_rt(pending);
-                    }
-                    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-                } else {
-                    wait_lgkmcnt<0>();
-                }
-                static_for<FMV>([&](auto b) { tie(xf[cur][b]); });
-                __builtin_amdgcn_sched_barrier(0);
-                static_for<NM>([&](auto m_c) {
-                    constexpr int m = decltype(m_c)::value;
-                    constexpr int b = m / FN, a = m % FN;
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[BUF][kk][a], xf[cur][b], acc[a][b], 0, 0, 0);
-                    // first half of the slots: LDS reads of the next sub-step's token fragments, early
-                    // enough that their latency is covered by the MFMAs of the second half
-                    if constexpr (m < FMV) {
-                        if constexpr (kk + 1 < KK) {
-                            xf[nxt][m] = lds_read_b128<m * BLK>(sbase + fx_addr[kk + 1]);
-                        } else {
-                            if (next) xf[nxt][m] = lds_read_b128<m * BLK>(nbase + fx_addr[0]);
-                        }
-                    }
-                    // the step's NL loads (weights of stage kt+WPF first, then tokens of stage kt+DX)
-                    // are spread evenly over the MFMA slots of all sub-steps but the last: the four
-                    // wavefronts run in lockstep, and bursts of back-to-back loads from all of them
-                    // exceed what the compute unit's one vector-memory pipe takes per cycle
-                    if constexpr (kk < KK - 1) {
-                        constexpr int slot = kk * NM + m, S = (KK - 1) * NM;
-                        static_for<NL>([&](auto i_c) {
-                            constexpr int i = decltype(i_c)::value;
-                            if constexpr ((i * S) / NL == slot) {
-                                if constexpr (i < WL) {
-                                    if (more_w) load_w_one(kt + WPF, std::integral_constant<int, NBUF>{}, std::integral_constant<int, i>{});
-                                } else {
-                                    if (more_x) issue_x_one(kt + DX, i - WL);
-                                }
-                            }
-                        });
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                });
-            });
-        };
-        using T_ = std::true_type;
-        using F_ = std::false_type;
-        using B0 = std::integral_constant<int, 0>;
-        using B1 = std::integral_constant<int, 1>;
-        using B2 = std::integral_constant<int, 2>;
-        static_assert(WPF == 2, "the loops below rotate three weight buffers");
-        // first step, then the steady steps three at a time, then whatever is left (generic)
-        step(0, B0{}, F_{});
-        int kt = 1;
-        for (; kt + 2 + DX < KT; kt += 3) {
-            step(kt, B1{}, T_{});
-            step(kt + 1, B2{}, T_{});
-            step(kt + 2, B0{}, T_{});
-        }
-        for (; kt < KT; kt += 3) {
-            step(kt, B1{}, F_{});
-            if (kt + 1 < KT) step(kt + 1, B2{}, F_{});
-            if (kt + 2 < KT) step(kt + 2, B0{}, F_{});
-        }
-    };
-
-    switch (fmv) {
-#define CASE(n)                                                        \
-    case n:                                                            \
-        if constexpr (n <= FM) main_loop(std::integral_constant<int, (n <= FM ? n : 1)>{}); \
-        break;
-        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
-#undef CASE
-        default: break;
-    }
-
-    gemm_epilogue<FM, FN, BM, TN, EPI>(acc, td, Np, C, ldc, 0, wave, lane);
-}
-
-
 // ------------------------------------------------------------------------------------------------
-// Device-side work list.  The rows of expert e are cut into ceil(n_e / bm) row tiles of nearly
-// equal height (a multiple of 32 rows, at most bm): an expert slightly larger than a multiple of
-// the tile height does not get a nearly empty extra tile, its rows are spread over taller tiles.
+// Device-side work list.  The rows of expert e are cut into ceil(n_e / cap) row tiles of nearly
+// equal height (a multiple of 32 rows, at most cap): an expert slightly larger than a multiple of
+// the cap does not get a nearly empty extra tile, its rows are spread over its tiles.
+//
+// The cap itself is chosen per GEMM from {bm, bm-32, ..., ~5/8 bm} on the device, from the actual
+// loads: a launch runs in ceil(work items / compute units) rounds of roughly one tile time each, so
+// when there are only a few rounds (the second expert GEMM has few weight-row tiles) a slightly
+// lower cap that fills the last round beats the tallest tile -- the tile-boundary staircase of
+// Sec. 3.3.2, seen from the scheduler's side.  Estimated time of a cap, in units of one 32-row
+// block of MFMA work: rounds * (mean tile height in blocks + SCHED_TILE_OVERHEAD).
+//
 // The list order is expert-major, then weight-row tile, then row tile (fastest); chunks of 4
 // consecutive items (row tiles sharing a weight panel) are dealt round-robin to the 8 XCDs, so the
 // workgroups resident on one XCD reuse weight panels in that XCD's L2 and every XCD gets the same
 // amount of work whatever the number of weight-row tiles.
 // ------------------------------------------------------------------------------------------------
 constexpr int SCHED_CHUNK = 4;
+constexpr int SCHED_CU = 256;                  // compute units of the device (one workgroup each)
+// Per-tile cost that does not scale with the tile's height, in 32-row blocks of MFMA work: every
+// tile streams its whole 256-row weight panel whatever its height.  Fitted to measured launch times
+// of the Mixtral-shape GEMMs at caps of 192 and 256 rows (tile time ~ blocks + 3.4).
+constexpr float SCHED_TILE_OVERHEAD = 3.5f;
+static __host__ __device__ inline int sched_min_cap_blocks(int bm) { return (5 * (bm / 32) + 7) / 8; }
 static inline int sched_grid(int mt_max, int nt) {
     const int chunks = (mt_max * nt + SCHED_CHUNK - 1) / SCHED_CHUNK;
     return 8 * SCHED_CHUNK * ((chunks + 7) / 8);
@@ -411,31 +40,58 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
     __shared__ int32_t pre[257];  // exclusive prefix of row tiles per expert; pre[E_local] = total
     __shared__ int32_t off[257];
     __shared__ int32_t scan[256];
+    __shared__ int32_t cand_tiles[8];
+    __shared__ int32_t total_blocks;
     const int tid = threadIdx.x;
-    int mt = 0;
     // host_rows >= 0: one group of host_rows rows (the router GEMM), no offsets array to read
+    int nblk_e = 0;  // 32-row blocks of expert tid
     if (tid < E_local) {
-        int n = host_rows >= 0 ? host_rows : offsets[tid + 1] - offsets[tid];
-        mt = (n + bm - 1) / bm;
+        const int n = host_rows >= 0 ? host_rows : offsets[tid + 1] - offsets[tid];
+        nblk_e = (n + 31) / 32;
     }
     for (int i = tid; i <= E_local; i += 256) off[i] = host_rows >= 0 ? i * host_rows : offsets[i];
-    scan[tid] = mt;
-    __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {
-        int v = tid >= o ? scan[tid - o] : 0;
-        __syncthreads();
-        scan[tid] += v;
-        __syncthreads();
-    }
-    pre[tid + 1] = scan[tid];
-    if (tid == 0) pre[0] = 0;
-    __syncthreads();
-    const int MT = pre[E_local];
+    const int hmax = bm / 32, hmin = sched_min_cap_blocks(bm);
 
     for (int which = 0; which < 2; ++which) {
         const int nt = which ? nt2 : nt1;
         const int grid = which ? grid2 : grid1;
         TileDesc* table = which ? t2 : t1;
+        if (grid <= 0) continue;  // uniform
+        // ---- pick the cap: tiles per candidate, summed over the experts ------------------------
+        if (tid < 8) cand_tiles[tid] = 0;
+        if (tid == 0) total_blocks = 0;
+        __syncthreads();
+        if (nblk_e > 0) {
+            for (int h = hmax; h >= hmin; --h) atomicAdd(&cand_tiles[hmax - h], (nblk_e + h - 1) / h);
+            atomicAdd(&total_blocks, nblk_e);
+        }
+        __syncthreads();
+        int cap = hmax;
+        float best = 3.0e38f;
+        for (int h = hmax; h >= hmin; --h) {
+            const int tiles = cand_tiles[hmax - h];
+            if (tiles <= 0) break;
+            const int rounds = (tiles * nt + SCHED_CU - 1) / SCHED_CU;
+            const float est = (float)rounds * ((float)total_blocks / (float)tiles + SCHED_TILE_OVERHEAD);
+            if (est < best) {  // ties keep the taller tile
+                best = est;
+                cap = h;
+            }
+        }
+        // ---- prefix of row tiles per expert ----------------------------------------------------
+        scan[tid] = (nblk_e + cap - 1) / cap;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {
+            int v = tid >= o ? scan[tid - o] : 0;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        pre[tid + 1] = scan[tid];
+        if (tid == 0) pre[0] = 0;
+        __syncthreads();
+        const int MT = pre[E_local];
+
         for (int b = blockIdx.x * 256 + tid; b < grid; b += gridDim.x * 256) {
             // XCD-aware order: the linear list (expert-major, then weight-row tile, then row tile) is
             // cut into chunks of SCHED_CHUNK consecutive items -- row tiles that share one weight
@@ -468,28 +124,24 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
             }
             table[b] = td;
         }
+        __syncthreads();  // pre[] and the candidate counters are rewritten for the second table
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// Host side: tile classes, plans, launches.
-// Classes 0 and 1 are the production token-tile classes (row tiles of up to 128 rows for very low
-// loads, up to 256 rows otherwise); higher ids are alternatives kept for tuning runs
-// (moe_set_tile_class).
-//   V(id, BM, NSX)
+// Host side: tile classes, plans, launches.  Class ids index the variants listed in
+// moe_gemm_kernel.h: 0 = 128-row tiles (very low loads), 1 = 256-row tiles (main), 2 = 64, 3 = 32.
 // ------------------------------------------------------------------------------------------------
-#define FOR_EACH_VARIANT(V) \
-    V(0, 128, 4)            \
-    V(1, 256, 4)            \
-    V(2, 64, 4)             \
-    V(3, 32, 4)
-
-static const int kClassRows[GEMM_NUM_CLASSES] = {
-#define V(id, bm, ns) bm,
-    FOR_EACH_VARIANT(V)
-#undef V
-};
+static const int kClassRows[GEMM_NUM_CLASSES] = {128, 256, 64, 32};
 constexpr int GEMM_BN = 256;
+
+#define DECL(name)                                                                                         \
+    hipError_t gemm_set_attr_##name();                                                                     \
+    hipError_t gemm_launch_##name(int cls, int grid, const uint16_t* X, int ldx, const int32_t* row_map,   \
+                                  const uint16_t* Wf, int Np, int K, uint16_t* C, int ldc,                 \
+                                  const TileDesc* table, hipStream_t st);
+DECL(swiglu) DECL(plain) DECL(pairsum)
+#undef DECL
 
 int gemm_class_rows(int cls) { return kClassRows[cls]; }
 
@@ -506,7 +158,8 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) 
     p.bm = kClassRows[cls];
     p.bn = GEMM_BN;
     int64_t extra = n_rows_cap < E_local ? n_rows_cap : E_local;
-    p.mt_max = (int)(n_rows_cap / p.bm + extra);
+    // upper bound on the row tiles at the lowest cap the scheduler may pick
+    p.mt_max = (int)(n_rows_cap / (32 * sched_min_cap_blocks(p.bm)) + extra);
     p.nt1 = (2 * f + p.bn - 1) / p.bn;
     p.nt2 = (d + p.bn - 1) / p.bn;
     p.grid1 = sched_grid(p.mt_max, p.nt1);
@@ -514,33 +167,11 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) 
     return p;
 }
 
-template <int BM, int NSX, int EPI>
-struct Variant {
-    static constexpr size_t smem = (size_t)NSX * BM * 64 * 2;
-    static hipError_t set_attr() {
-        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, NSX, EPI>,
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    }
-    static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wf,
-                             int Np, int K, uint16_t* C, int ldc, const TileDesc* table, hipStream_t st) {
-        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI>), dim3(grid), dim3(256), smem, st, X, ldx, row_map,
-                           Wf, Np, K, C, ldc, table);
-        return hipGetLastError();
-    }
-};
-
 hipError_t gemm_init_attributes() {
-    hipError_t err;
-#define V(id, bm, ns)                                   \
-    err = Variant<bm, ns, EPI_SWIGLU>::set_attr();      \
-    if (err != hipSuccess) return err;                  \
-    err = Variant<bm, ns, EPI_PLAIN>::set_attr();       \
-    if (err != hipSuccess) return err;                  \
-    err = Variant<bm, ns, EPI_PAIR_SUM_F32>::set_attr(); \
-    if (err != hipSuccess) return err;
-    FOR_EACH_VARIANT(V)
-#undef V
-    return hipSuccess;
+    hipError_t err = gemm_set_attr_swiglu();
+    if (err == hipSuccess) err = gemm_set_attr_plain();
+    if (err == hipSuccess) err = gemm_set_attr_pairsum();
+    return err;
 }
 
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1, TileDesc* t2,
@@ -557,25 +188,13 @@ hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_loca
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table, hipStream_t st) {
     if (p.grid1 <= 0) return hipSuccess;
-    switch (p.cls) {
-#define V(id, bm, ns) \
-    case id: return Variant<bm, ns, EPI_SWIGLU>::launch(p.grid1, X, ldx, row_map, W13f, 2 * f, d, H, moe_ld_pad(f), table, st);
-        FOR_EACH_VARIANT(V)
-#undef V
-    }
-    return hipErrorInvalidValue;
+    return gemm_launch_swiglu(p.cls, p.grid1, X, ldx, row_map, W13f, 2 * f, d, H, moe_ld_pad(f), table, st);
 }
 
 hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2f, int d, int f, uint16_t* Y,
                         const TileDesc* table, hipStream_t st) {
     if (p.grid2 <= 0) return hipSuccess;
-    switch (p.cls) {
-#define V(id, bm, ns) \
-    case id: return Variant<bm, ns, EPI_PLAIN>::launch(p.grid2, H, moe_ld_pad(f), nullptr, W2f, d, f, Y, d, table, st);
-        FOR_EACH_VARIANT(V)
-#undef V
-    }
-    return hipErrorInvalidValue;
+    return gemm_launch_plain(p.cls, p.grid2, H, moe_ld_pad(f), nullptr, W2f, d, f, Y, d, table, st);
 }
 
 // ---- router logits as a one-group GEMM (E >= 32): logits[T, Ep] = x[T, d] * Wg, fp32 ------------
@@ -594,7 +213,7 @@ int router_gemm_grid_max(int T_max, int Rp) {
     const int nt = (Rp + GEMM_BN - 1) / GEMM_BN;
     int g = 0;
     for (int c = 0; c < GEMM_NUM_CLASSES; ++c) {
-        int gc = sched_grid(T_max / kClassRows[c] + 1, nt);
+        int gc = sched_grid(T_max / (32 * sched_min_cap_blocks(kClassRows[c])) + 1, nt);
         if (gc > g) g = gc;
     }
     return g;
@@ -604,16 +223,10 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
                               TileDesc* table, hipStream_t st) {
     const int c = router_gemm_pick(T, Rp);
     const int nt = (Rp + GEMM_BN - 1) / GEMM_BN;
-    const int grid = sched_grid(T / kClassRows[c] + 1, nt);
+    const int grid = sched_grid(T / (32 * sched_min_cap_blocks(kClassRows[c])) + 1, nt);
     hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
                        kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    switch (c) {
-#define V(id, bm, ns) \
-    case id: return Variant<bm, ns, EPI_PAIR_SUM_F32>::launch(grid, x, d, nullptr, rp, Rp, d, (uint16_t*)logits, ldl, table, st);
-        FOR_EACH_VARIANT(V)
-#undef V
-    }
-    return hipErrorInvalidValue;
+    return gemm_launch_pairsum(c, grid, x, d, nullptr, rp, Rp, d, (uint16_t*)logits, ldl, table, st);
 }
