@@ -30,7 +30,7 @@ bool shape_ok(const moe_shape* s) {
 }
 
 struct Layout {
-    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, table_r, logits, H, Y, total;
+    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, table_r, logits, route_ws, H, Y, total;
     int table1_cap, table2_cap;
     int64_t rows_cap;
 };
@@ -64,10 +64,11 @@ Layout make_layout(const moe_shape* s) {
     if (s->E >= MOE_ROUTER_GEMM_MIN_E) {
         const int cap = router_gemm_grid_max(s->T_max, moe_router_packed_rows(s->E));
         L.table_r = take((size_t)cap * sizeof(TileDesc));
-        L.logits = take((size_t)s->T_max * moe_router_cols(s->E) * 4);
+        L.logits = take((size_t)moe_router_split_cap(s->T_max) * s->T_max * moe_router_cols(s->E) * 4);
     } else {
         L.table_r = L.logits = 0;
     }
+    L.route_ws = take((size_t)MOE_ROUTE_WS_INTS * 4);
     L.H = take((size_t)L.rows_cap * moe_ld_pad(s->f) * 2);
     L.Y = take((size_t)L.rows_cap * s->d * 2);
     L.total = o;
@@ -118,6 +119,7 @@ size_t moe_workspace_bytes(const moe_shape* s) {
 size_t moe_packed_router_bytes(const moe_shape* s) {
     if (!shape_ok(s)) return 0;
     if (s->E >= MOE_ROUTER_GEMM_MIN_E) return (size_t)moe_router_packed_rows(s->E) * s->d * 2;
+    if (moe_router_resident(s->E, s->d)) return (size_t)16 * s->d * 2;
     return (size_t)2 * moe_router_rows(s->E) * s->d * 2;
 }
 
@@ -165,6 +167,7 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     c->table1 = (TileDesc*)(c->ws + L.table1);
     c->table2 = (TileDesc*)(c->ws + L.table2);
     c->table_r = (TileDesc*)(c->ws + L.table_r);
+    c->route_ws = (int32_t*)(c->ws + L.route_ws);
     c->logits = (float*)(c->ws + L.logits);
     c->H = (uint16_t*)(c->ws + L.H);
     c->Y = (uint16_t*)(c->ws + L.Y);
@@ -175,6 +178,12 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     c->ev_count = 0;
     c->last_cls = -1;
     c->forced_cls = -1;
+    // the resident router's ticket counter must be zero before the first launch (each launch leaves
+    // it at zero again); synchronous, creation is not on the hot path
+    if (note_hip(hipMemset(c->route_ws, 0, (size_t)MOE_ROUTE_WS_INTS * 4), "hipMemset(workspace)") != MOE_OK) {
+        delete c;
+        return MOE_ERR_DEVICE;
+    }
     if (s->flags & MOE_FLAG_STAGE_EVENTS) {
         c->ev = new (std::nothrow) hipEvent_t[MOE_EVENT_RING][MOE_NUM_STAGES + 1];
         if (c->ev == nullptr) {
@@ -232,6 +241,12 @@ moe_status moe_pack_weights(moe_ctx* c, const void* W1, const void* W3, const vo
                                         (hipStream_t)stream));
 }
 
+// partial-logit slabs of T tokens that fit the workspace sized for T_max
+static int logits_slabs(const moe_ctx* c, int T) {
+    int64_t n = (int64_t)moe_router_split_cap(c->s.T_max) * c->s.T_max / (T > 0 ? T : 1);
+    return n > 8 ? 8 : (int)n;
+}
+
 moe_status moe_route(moe_ctx* c, const void* x, const void* rp, const float* bias, int32_t T,
                      int32_t* topk_idx, float* topk_w, int32_t* counts, void* stream) {
     if (c == nullptr || T < 0 || T > c->s.T_max) return MOE_ERR_INVALID_ARG;
@@ -240,7 +255,8 @@ moe_status moe_route(moe_ctx* c, const void* x, const void* rp, const float* bia
     if (bias != nullptr && !aligned(bias, 4)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     return from_hip(launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, c->s.d, c->s.E, c->s.k,
-                                 topk_idx, topk_w, counts, c->logits, c->table_r, (hipStream_t)stream));
+                                 topk_idx, topk_w, counts, c->logits, logits_slabs(c, T), c->table_r, c->route_ws,
+                                 (hipStream_t)stream));
 }
 
 moe_status moe_permute(moe_ctx* c, const void* x, const int32_t* topk_idx, int32_t T, void* xp,
@@ -310,7 +326,7 @@ moe_status moe_layer_forward(moe_ctx* c, const void* x, const void* rp, const fl
 
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_ROUTE], st);
     hipError_t e = launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, s.d, s.E, s.k, c->idx, c->w,
-                                counts, c->logits, c->table_r, st);
+                                counts, c->logits, logits_slabs(c, T), c->table_r, c->route_ws, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_PERMUTE], st);
     e = launch_permute(c->idx, T, s.k, s.e_lo, s.E_local, c->blockhist, c->offsets, c->row_of, c->tok_of, st);

@@ -139,7 +139,7 @@ constexpr int GEMM_BN = 256;
     hipError_t gemm_set_attr_##name();                                                                     \
     hipError_t gemm_launch_##name(int cls, int grid, const uint16_t* X, int ldx, const int32_t* row_map,   \
                                   const uint16_t* Wf, int Np, int K, uint16_t* C, int ldc,                 \
-                                  const TileDesc* table, hipStream_t st);
+                                  const TileDesc* table, int nsplit, size_t c_split_bytes, hipStream_t st);
 DECL(swiglu) DECL(plain) DECL(pairsum)
 #undef DECL
 
@@ -188,25 +188,35 @@ hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_loca
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table, hipStream_t st) {
     if (p.grid1 <= 0) return hipSuccess;
-    return gemm_launch_swiglu(p.cls, p.grid1, X, ldx, row_map, W13f, 2 * f, d, H, moe_ld_pad(f), table, st);
+    return gemm_launch_swiglu(p.cls, p.grid1, X, ldx, row_map, W13f, 2 * f, d, H, moe_ld_pad(f), table, 1, 0, st);
 }
 
 hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2f, int d, int f, uint16_t* Y,
                         const TileDesc* table, hipStream_t st) {
     if (p.grid2 <= 0) return hipSuccess;
-    return gemm_launch_plain(p.cls, p.grid2, H, moe_ld_pad(f), nullptr, W2f, d, f, Y, d, table, st);
+    return gemm_launch_plain(p.cls, p.grid2, H, moe_ld_pad(f), nullptr, W2f, d, f, Y, d, table, 1, 0, st);
 }
 
 // ---- router logits as a one-group GEMM (E >= 32): logits[T, Ep] = x[T, d] * Wg, fp32 ------------
 // Router rows are packed like W1|W3: 32-row blocks alternate between the high and the low bf16 term
-// of the same 32 experts, and the epilogue adds the two accumulators.
-static int router_gemm_pick(int T, int Rp) {
-    // tallest row tile that still gives every compute unit a work item
-    const int nt = (Rp + GEMM_BN - 1) / GEMM_BN;
-    int best = 3;  // 32 rows
-    for (int c = 0; c < GEMM_NUM_CLASSES; ++c)
-        if ((T / kClassRows[c]) * nt >= 256 && kClassRows[c] > kClassRows[best]) best = c;
-    return best;
+// of the same 32 experts, and the epilogue adds the two accumulators.  The output is tiny next to the
+// reduction length, so the reduction is split over up to 8 workgroups per tile (partial logits in
+// consecutive [T, ldl] slabs, added in order by the top-k kernel) until every compute unit has work.
+struct RouterPick { int cls, nsplit; };
+static RouterPick router_gemm_pick(int T, int d, int Rp, int max_split) {
+    const int nt = (Rp + GEMM_BN - 1) / GEMM_BN, KT = d / 64;
+    static const int order[GEMM_NUM_CLASSES] = {1, 0, 2, 3};  // tallest tile first
+    for (int i = 0; i < GEMM_NUM_CLASSES; ++i) {
+        const int c = order[i];
+        const int mt = (T + kClassRows[c] - 1) / kClassRows[c];
+        for (int s = 1; s <= 8 && s <= max_split; ++s)
+            if (KT % s == 0 && KT / s >= 8 && mt * nt * s >= SCHED_CU) return {c, s};
+    }
+    // not enough work for the whole device whatever the shape: the 128-row tile, deepest allowed split
+    int s = 1;
+    for (int t = 2; t <= 8 && t <= max_split; ++t)
+        if (KT % t == 0 && KT / t >= 8) s = t;
+    return {0, s};
 }
 
 int router_gemm_grid_max(int T_max, int Rp) {
@@ -220,13 +230,16 @@ int router_gemm_grid_max(int T_max, int Rp) {
 }
 
 hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
-                              TileDesc* table, hipStream_t st) {
-    const int c = router_gemm_pick(T, Rp);
+                              int max_split, int* nsplit_out, TileDesc* table, hipStream_t st) {
+    const RouterPick pk = router_gemm_pick(T, d, Rp, max_split);
+    const int c = pk.cls;
     const int nt = (Rp + GEMM_BN - 1) / GEMM_BN;
     const int grid = sched_grid(T / (32 * sched_min_cap_blocks(kClassRows[c])) + 1, nt);
+    *nsplit_out = pk.nsplit;
     hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
                        kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    return gemm_launch_pairsum(c, grid, x, d, nullptr, rp, Rp, d, (uint16_t*)logits, ldl, table, st);
+    return gemm_launch_pairsum(c, grid, x, d, nullptr, rp, Rp, d / pk.nsplit, (uint16_t*)logits, ldl, table, pk.nsplit,
+                               (size_t)T * ldl * sizeof(float), st);
 }

@@ -167,12 +167,17 @@ static __device__ inline void wait_vmcnt_rt(int n) {
     }
 }
 
+// Split K (gridDim.y > 1, used by the router-logit GEMM whose output is tiny next to its reduction
+// length): workgroup (x, y) reduces over elements [y*K, (y+1)*K) of the K_total = gridDim.y * K long
+// reduction dimension and writes its partial result c_split_bytes behind that of split y-1; the
+// consumer adds the partial results in a fixed order.
 template <int BM, int NSX, int EPI>
 __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
                                                       const int32_t* __restrict__ row_map,
                                                       const uint16_t* __restrict__ Wf, int Np, int K,
                                                       uint16_t* __restrict__ C, int ldc,
-                                                      const TileDesc* __restrict__ table) {
+                                                      const TileDesc* __restrict__ table,
+                                                      size_t c_split_bytes) {
     constexpr int BN = 256, BK = 64, NW = 4, TN = BN / NW, FN = TN / 32, FM = BM / 32;
     constexpr int CH = BK / 8;   // 16-byte chunks per staged token row
     constexpr int RPL = 64 / CH; // rows covered by one wave-level load
@@ -197,6 +202,9 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
     const int frow = lane & 31, fhalf = lane >> 5;
     const int KT = K / BK;
     const int fmv = (td.rows + 31) / 32;  // valid 32-row blocks: the same for all four wavefronts
+    const int K_total = K * (int)gridDim.y;
+    X += (size_t)blockIdx.y * K;
+    C = (uint16_t*)((char*)C + (size_t)blockIdx.y * c_split_bytes);
 
     // token sources: pass p of a wavefront brings rows 32*p + 8*wave .. +8 of the tile (one pass per
     // 32-row block), 32-bit byte offsets from the wave-uniform base X + kt*BK
@@ -217,7 +225,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
     for (int a = 0; a < FN; ++a) {
         int nb = (td.n0 + wave * TN) / 32 + a;
         if (nb >= nbt) nb = nbt - 1;  // past the last weight row: computed, never stored
-        wsrc[a] = (const char*)(Wf + ((size_t)td.expert * nbt + nb) * ((size_t)K * 32));
+        wsrc[a] = (const char*)(Wf + ((size_t)td.expert * nbt + nb) * ((size_t)K_total * 32) + (size_t)blockIdx.y * K * 32);
     }
     const uint32_t wlane = (uint32_t)lane * 16u;
     // LDS byte address (inside a stage) of this lane's chunk of block 0 for every MFMA sub-step
@@ -409,10 +417,12 @@ struct Variant {
         return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, NSX, EPI>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
+    // K is the reduction length of ONE split; nsplit = 1 for the expert GEMMs
     static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wf,
-                             int Np, int K, uint16_t* C, int ldc, const TileDesc* table, hipStream_t st) {
-        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI>), dim3(grid), dim3(256), smem, st, X, ldx, row_map,
-                           Wf, Np, K, C, ldc, table);
+                             int Np, int K, uint16_t* C, int ldc, const TileDesc* table, int nsplit,
+                             size_t c_split_bytes, hipStream_t st) {
+        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI>), dim3(grid, nsplit), dim3(256), smem, st, X, ldx,
+                           row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
         return hipGetLastError();
     }
 };
@@ -427,7 +437,7 @@ struct Variant {
     }                                                                                                         \
     hipError_t gemm_launch_##name(int cls, int grid, const uint16_t* X, int ldx, const int32_t* row_map,      \
                                   const uint16_t* Wf, int Np, int K, uint16_t* C, int ldc,                    \
-                                  const TileDesc* table, hipStream_t st) {                                    \
+                                  const TileDesc* table, int nsplit, size_t c_split_bytes, hipStream_t st) {  \
         switch (cls) { FOR_EACH_VARIANT(MOE_GEMM_CASE_##EPI) }                                                \
         return hipErrorInvalidValue;                                                                          \
     }
@@ -435,7 +445,7 @@ struct Variant {
     err = Variant<bm, ns, EPI>::set_attr();       \
     if (err != hipSuccess) return err;
 #define MOE_GEMM_CASE(EPI, id, bm, ns) \
-    case id: return Variant<bm, ns, EPI>::launch(grid, X, ldx, row_map, Wf, Np, K, C, ldc, table, st);
+    case id: return Variant<bm, ns, EPI>::launch(grid, X, ldx, row_map, Wf, Np, K, C, ldc, table, nsplit, c_split_bytes, st);
 #define MOE_GEMM_SET_ATTR_EPI_PLAIN(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PLAIN, bm, ns)
 #define MOE_GEMM_SET_ATTR_EPI_SWIGLU(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_SWIGLU, bm, ns)
 #define MOE_GEMM_SET_ATTR_EPI_PAIR_SUM_F32(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PAIR_SUM_F32, bm, ns)

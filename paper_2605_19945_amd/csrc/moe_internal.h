@@ -49,6 +49,7 @@ struct moe_ctx {
     TileDesc* table2;    // [grid2_max]
     TileDesc* table_r;   // router GEMM work list (E >= MOE_ROUTER_GEMM_MIN_E)
     float* logits;       // [T_max, router cols] fp32 (E >= MOE_ROUTER_GEMM_MIN_E)
+    int32_t* route_ws;   // [MOE_ROUTE_WS_INTS] resident router: ticket (zero between launches) + partial counts
     uint16_t* H;         // [rows_cap, f] bf16
     uint16_t* Y;         // [rows_cap, d] bf16
     int64_t rows_cap;
@@ -67,6 +68,12 @@ static __host__ __device__ inline int moe_ld_pad(int K) { return K + 64; }
 // Routers with at least this many experts compute their logits with the tiled GEMM kernel; smaller
 // ones with the direct MFMA kernel.
 constexpr int MOE_ROUTER_GEMM_MIN_E = 32;
+// Routers this small keep their matrix in registers (persistent kernel, see moe_route.hip).
+static inline bool moe_router_resident(int E, int d) { return E <= 8 && d % 512 == 0 && d <= 4096; }
+// Router scratch (ints, all zero between launches): ticket + per-workgroup partial counts of the
+// resident router, then 32 sub-counters per expert of the top-k kernel (GEMM path).
+constexpr int MOE_ROUTE_WS_SUBCOUNTS = 1 + 256 * 8 + 63;
+constexpr int MOE_ROUTE_WS_INTS = MOE_ROUTE_WS_SUBCOUNTS + 32 * 256;
 static inline int moe_router_cols(int E) { return (E + 31) / 32 * 32; }       // logits row length (GEMM path)
 static inline int moe_router_packed_rows(int E) { return moe_router_cols(E) * 2; }  // hi/lo interleaved rows
 static inline int moe_router_rows(int E) {  // packed router rows: multiple of 16, power-of-two blocks
@@ -81,8 +88,8 @@ hipError_t launch_pack_router(const float* Wg, int d, int E, uint16_t* rp, hipSt
 hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uint16_t* W2, int E_local,
                                int d, int f, uint16_t* packed, hipStream_t st);
 hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias, int T, int d, int E,
-                        int k, int32_t* idx, float* w, int32_t* counts, float* logits_ws, TileDesc* table_ws,
-                        hipStream_t st);
+                        int k, int32_t* idx, float* w, int32_t* counts, float* logits_ws, int logits_slabs,
+                        TileDesc* table_ws, int32_t* route_ws, hipStream_t st);
 hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
                           int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st);
 hipError_t launch_gather(const uint16_t* x, const int32_t* tok_of, const int32_t* offsets, int E_local,
@@ -96,7 +103,9 @@ int gemm_class_rows(int cls);
 hipError_t gemm_init_attributes();
 int router_gemm_grid_max(int T_max, int Rp);
 hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
-                              TileDesc* table, hipStream_t st);
+                              int max_split, int* nsplit_out, TileDesc* table, hipStream_t st);
+// Slabs of partial router logits ([T, cols] fp32 each) the workspace holds for T tokens
+static inline int moe_router_split_cap(int T) { return T <= 8192 ? 8 : T <= 16384 ? 4 : T <= 32768 ? 2 : 1; }
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,
                            TileDesc* t2, hipStream_t st);
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,

@@ -50,6 +50,11 @@ ROUTE_CASES = [
     ("E128_top8", 300, 2048, 128, 8, 0.0221, 0.5),
     ("E256_top8", 200, 1024, 256, 8, 0.03125, 0.5),
     ("mixtral_d", 700, 4096, 8, 2, 0.02, 0.0),
+    # small routers whose matrix stays in registers (E <= 8, d a multiple of 512 up to 4096)
+    ("resident_E5_k5_bias", 333, 512, 5, 5, 0.05, 0.5),
+    ("resident_many_groups", 5000, 1024, 8, 3, 0.04, 0.3),
+    ("resident_one_token", 1, 512, 8, 2, 0.1, 0.0),
+    ("resident_E1", 40, 1536, 1, 1, 0.1, 0.0),
 ]
 
 

@@ -42,7 +42,7 @@ def test_status_strings(lib):
 def test_sizes_and_shape_validation(lib):
     ok = _Shape(4096, 4096, 14336, 8, 2, 0, 8, 0)
     assert lib.moe_packed_weight_bytes(C.byref(ok)) >= 3 * 8 * 4096 * 14336 * 2
-    assert lib.moe_packed_router_bytes(C.byref(ok)) == 2 * 16 * 4096 * 2
+    assert lib.moe_packed_router_bytes(C.byref(ok)) == 16 * 4096 * 2
     assert lib.moe_rows_capacity(C.byref(ok), 4096) == 8192
     ws = lib.moe_workspace_bytes(C.byref(ok))
     assert ws > 8192 * (14336 + 4096) * 2                  # holds H and Y
