@@ -16,32 +16,61 @@
 // Sec. 3.3.2, seen from the scheduler's side.  Estimated time of a cap, in units of one 32-row
 // block of MFMA work: rounds * (mean tile height in blocks + SCHED_TILE_OVERHEAD).
 //
-// The list order is expert-major, then weight-row tile, then row tile (fastest); chunks of 4
-// consecutive items (row tiles sharing a weight panel) are dealt round-robin to the 8 XCDs, so the
-// workgroups resident on one XCD reuse weight panels in that XCD's L2 and every XCD gets the same
-// amount of work whatever the number of weight-row tiles.
+// XCD-aware order.  Workgroup b runs on XCD b % 8.  A "piece" is C consecutive slots for row tiles of
+// one expert and one weight-row tile (they share that weight panel); C is the mean number of row
+// tiles per loaded expert (1..8), an expert with fewer row tiles leaves the last slots of its piece
+// empty, one with more has several pieces per weight-row tile.  Pieces are numbered expert-major,
+// then weight-row tile, and dealt round-robin to the XCDs.  So the workgroups resident on one XCD at
+// a time are a few consecutive weight-row tiles of one expert times its row tiles: a weight panel
+// is fetched into one L2 (one per piece), the token panels are shared by the pieces running side by
+// side, and every XCD gets the same number of slots.  Empty slots cost one workgroup that exits at
+// once; they number fewer than the row tiles.
 // ------------------------------------------------------------------------------------------------
-constexpr int SCHED_CHUNK = 4;
-constexpr int SCHED_CU = 256;                  // compute units of the device (one workgroup each)
+constexpr int SCHED_CU = 256;    // compute units of the device (one workgroup each)
+constexpr int SCHED_PIECE_MAX = 8;  // slots per piece, at most
 // Per-tile cost that does not scale with the tile's height, in 32-row blocks of MFMA work: every
 // tile streams its whole 256-row weight panel whatever its height.  Fitted to measured launch times
 // of the Mixtral-shape GEMMs at caps of 192 and 256 rows (tile time ~ blocks + 3.4).
 constexpr float SCHED_TILE_OVERHEAD = 3.5f;
 static __host__ __device__ inline int sched_min_cap_blocks(int bm) { return (5 * (bm / 32) + 7) / 8; }
-static inline int sched_grid(int mt_max, int nt) {
-    const int chunks = (mt_max * nt + SCHED_CHUNK - 1) / SCHED_CHUNK;
-    return 8 * SCHED_CHUNK * ((chunks + 7) / 8);
+// upper bound on the slots of a launch: padded row tiles < 2 * row tiles, rounded up to whole rounds
+// of 8 pieces
+static inline int sched_grid(int mt_max, int nt) { return 2 * mt_max * nt + 8 * SCHED_PIECE_MAX; }
+
+// inclusive prefix sum over the 64 lanes with data-parallel-primitive moves: a Kogge-Stone scan inside
+// each row of 16 lanes, then the row totals are carried into the following rows
+static __device__ inline int wave_scan_incl(int v) {
+#define DPP_ADD(ctrl, row_mask) v += __builtin_amdgcn_update_dpp(0, v, ctrl, row_mask, 0xf, false);
+    DPP_ADD(0x111, 0xf)  // row_shr:1
+    DPP_ADD(0x112, 0xf)  // row_shr:2
+    DPP_ADD(0x114, 0xf)  // row_shr:4
+    DPP_ADD(0x118, 0xf)  // row_shr:8
+    DPP_ADD(0x142, 0xa)  // row_bcast:15 into rows 1 and 3
+    DPP_ADD(0x143, 0xc)  // row_bcast:31 into rows 2 and 3
+#undef DPP_ADD
+    return v;
+}
+// inclusive scan of one int per thread over the 256 threads of the workgroup; part: 4 ints of LDS
+// scratch; two barriers
+static __device__ inline int block_scan_incl(int v, int32_t* part) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v = wave_scan_incl(v);
+    __syncthreads();  // part[] may still be read from a previous call
+    if (lane == 63) part[wave] = v;
+    __syncthreads();
+    for (int ww = 0; ww < wave; ++ww) v += part[ww];
+    return v;
 }
 
 __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict__ offsets, int E_local,
                                                        int bm, int bn, int nt1, int grid1,
                                                        TileDesc* __restrict__ t1, int nt2, int grid2,
                                                        TileDesc* __restrict__ t2, int host_rows) {
-    __shared__ int32_t pre[257];  // exclusive prefix of row tiles per expert; pre[E_local] = total
-    __shared__ int32_t off[257];
-    __shared__ int32_t scan[256];
-    __shared__ int32_t cand_tiles[8];
-    __shared__ int32_t total_blocks;
+    __shared__ int32_t s_off[257];
+    __shared__ int32_t s_mte[256];   // row tiles of expert e
+    __shared__ int32_t s_pre[257];   // pieces per weight-row tile of the experts before e; [E_local] = total
+    __shared__ int32_t s_part[4];
+    __shared__ int32_t s_tot[6][4];
     const int tid = threadIdx.x;
     // host_rows >= 0: one group of host_rows rows (the router GEMM), no offsets array to read
     int nblk_e = 0;  // 32-row blocks of expert tid
@@ -49,82 +78,93 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
         const int n = host_rows >= 0 ? host_rows : offsets[tid + 1] - offsets[tid];
         nblk_e = (n + 31) / 32;
     }
-    for (int i = tid; i <= E_local; i += 256) off[i] = host_rows >= 0 ? i * host_rows : offsets[i];
+    for (int i = tid; i <= E_local; i += 256) s_off[i] = host_rows >= 0 ? i * host_rows : offsets[i];
     const int hmax = bm / 32, hmin = sched_min_cap_blocks(bm);
+    // totals over the experts: 32-row blocks, loaded experts, row tiles for every candidate cap (<= 4)
+    int tot[6];
+    tot[0] = nblk_e;
+    tot[5] = nblk_e > 0 ? 1 : 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int h = hmax - c;
+        tot[c + 1] = (h >= hmin && nblk_e > 0) ? (nblk_e + h - 1) / h : 0;
+    }
+    {
+        const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+        for (int c = 0; c < 6; ++c) {
+            const int incl = wave_scan_incl(tot[c]);
+            if (lane == 63) s_tot[c][wave] = incl;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < 6; ++c) tot[c] = s_tot[c][0] + s_tot[c][1] + s_tot[c][2] + s_tot[c][3];
+    }
 
     for (int which = 0; which < 2; ++which) {
         const int nt = which ? nt2 : nt1;
         const int grid = which ? grid2 : grid1;
         TileDesc* table = which ? t2 : t1;
         if (grid <= 0) continue;  // uniform
-        // ---- pick the cap: tiles per candidate, summed over the experts ------------------------
-        if (tid < 8) cand_tiles[tid] = 0;
-        if (tid == 0) total_blocks = 0;
-        __syncthreads();
-        if (nblk_e > 0) {
-            for (int h = hmax; h >= hmin; --h) atomicAdd(&cand_tiles[hmax - h], (nblk_e + h - 1) / h);
-            atomicAdd(&total_blocks, nblk_e);
-        }
-        __syncthreads();
-        int cap = hmax;
+        // ---- pick the cap --------------------------------------------------------------------
+        int cap = hmax, MT = 0;
         float best = 3.0e38f;
-        for (int h = hmax; h >= hmin; --h) {
-            const int tiles = cand_tiles[hmax - h];
-            if (tiles <= 0) break;
-            const int rounds = (tiles * nt + SCHED_CU - 1) / SCHED_CU;
-            const float est = (float)rounds * ((float)total_blocks / (float)tiles + SCHED_TILE_OVERHEAD);
-            if (est < best) {  // ties keep the taller tile
-                best = est;
-                cap = h;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int tiles = tot[c + 1];
+            if (tiles > 0) {
+                const int rounds = (tiles * nt + SCHED_CU - 1) / SCHED_CU;
+                const float est = (float)rounds * ((float)tot[0] / (float)tiles + SCHED_TILE_OVERHEAD);
+                if (est < best) {  // ties keep the taller tile
+                    best = est;
+                    cap = hmax - c;
+                    MT = tiles;
+                }
             }
         }
-        // ---- prefix of row tiles per expert ----------------------------------------------------
-        scan[tid] = (nblk_e + cap - 1) / cap;
+        // ---- pieces: C slots each, C = mean row tiles per loaded expert ----------------------------
+        int C = tot[5] > 0 ? (MT + tot[5] / 2) / tot[5] : 1;
+        C = C < 1 ? 1 : (C > SCHED_PIECE_MAX ? SCHED_PIECE_MAX : C);
+        const int mte_mine = (nblk_e + cap - 1) / cap;
+        const int pp_incl = block_scan_incl((mte_mine + C - 1) / C, s_part);
+        __syncthreads();  // s_mte / s_pre of the previous table are no longer read
+        s_mte[tid] = mte_mine;
+        s_pre[tid + 1] = pp_incl;
+        if (tid == 0) s_pre[0] = 0;
         __syncthreads();
-        for (int o = 1; o < 256; o <<= 1) {
-            int v = tid >= o ? scan[tid - o] : 0;
-            __syncthreads();
-            scan[tid] += v;
-            __syncthreads();
-        }
-        pre[tid + 1] = scan[tid];
-        if (tid == 0) pre[0] = 0;
-        __syncthreads();
-        const int MT = pre[E_local];
+        const int n_pieces = s_pre[E_local] * nt;
 
         for (int b = blockIdx.x * 256 + tid; b < grid; b += gridDim.x * 256) {
-            // XCD-aware order: the linear list (expert-major, then weight-row tile, then row tile) is
-            // cut into chunks of SCHED_CHUNK consecutive items -- row tiles that share one weight
-            // panel -- and the chunks are dealt round-robin to the 8 XCDs (work item b runs on XCD b % 8)
             const int x = b & 7, slot = b >> 3;
-            const int L = ((slot / SCHED_CHUNK) * 8 + x) * SCHED_CHUNK + slot % SCHED_CHUNK;
+            const int piece = (slot / C) * 8 + x, pos = slot % C;
             TileDesc td;
             td.expert = 0; td.row0 = 0; td.rows = 0; td.n0 = 0;
-            if (L < MT * nt) {
-                // largest e with pre[e] * nt <= L  (that expert has at least one row tile)
+            if (piece < n_pieces) {
+                // the expert e with s_pre[e] * nt <= piece < s_pre[e + 1] * nt
                 int lo = 0, hi = E_local;
                 while (hi - lo > 1) {
                     int mid = (lo + hi) >> 1;
-                    if (pre[mid] * nt <= L) lo = mid; else hi = mid;
+                    if (s_pre[mid] * nt <= piece) lo = mid; else hi = mid;
                 }
                 const int e = lo;
-                const int mte = pre[e + 1] - pre[e];
-                const int r = L - pre[e] * nt;
-                const int mi = r % mte, ni = r / mte;
-                const int e_rows = off[e + 1] - off[e];
-                // 32-row blocks of the expert, dealt evenly to its mte tiles
-                const int nblk = (e_rows + 31) / 32;
-                const int base = nblk / mte, rem = nblk % mte;
-                const int blk0 = mi * base + min(mi, rem);
-                const int nb = base + (mi < rem ? 1 : 0);
-                td.expert = e;
-                td.row0 = off[e] + blk0 * 32;
-                td.rows = min(nb * 32, e_rows - blk0 * 32);
-                td.n0 = ni * bn;
+                const int mte = s_mte[e], pp = s_pre[e + 1] - s_pre[e];
+                const int q = piece - s_pre[e] * nt;
+                const int ni = q / pp, mi = (q % pp) * C + pos;
+                if (mi < mte) {
+                    const int e_rows = s_off[e + 1] - s_off[e];
+                    // 32-row blocks of the expert, dealt evenly to its mte tiles
+                    const int nblk = (e_rows + 31) / 32;
+                    const int base = nblk / mte, rem = nblk % mte;
+                    const int blk0 = mi * base + min(mi, rem);
+                    const int nb = base + (mi < rem ? 1 : 0);
+                    td.expert = e;
+                    td.row0 = s_off[e] + blk0 * 32;
+                    td.rows = min(nb * 32, e_rows - blk0 * 32);
+                    td.n0 = ni * bn;
+                }
             }
             table[b] = td;
         }
-        __syncthreads();  // pre[] and the candidate counters are rewritten for the second table
     }
 }
 
