@@ -126,6 +126,46 @@ def run_curve(moe, gu, weights_dev_packed, args):
         json.dump({"workload": "mixtral_skewed", "rows": rows}, fh, indent=1)
 
 
+def run_profile_curve(moe, s, packed, args):
+    """Token-vs-latency curve of the isolated expert kernels, sampled at the tile boundaries
+    (paper Sec. 3.3.2, Step-2) -> gpurun_out/cg_curve.json."""
+    import torch
+    from paper_2605_19945_amd import latency_curve as lc
+    boundary = s.E_local * 32            # row tiles grow in steps of 32 rows per expert
+    dense_max = s.E_local * 2048         # every boundary up to 2K tokens per expert
+    n_max, sparse_step = 4 * dense_max, dense_max // 2
+    after = s.E_local                    # n = m*boundary + E_local: every expert has crossed its boundary
+    counts = lc.sample_counts(boundary, dense_max, n_max, sparse_step, after)
+    ctx = moe.MoEContext(n_max, s.d, s.f, s.E_local, 1)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(args.seed)
+    xp = torch.randn(n_max, s.d, device="cuda", generator=g).bfloat16()
+    t0 = time.perf_counter()
+    ms = ctx.moe_profile_ffn(xp, packed, counts, warmup=2, iters=args.profile_iters)
+    wall = time.perf_counter() - t0
+    curve = lc.LatencyCurve(counts, ms)
+    dense_end = min(dense_max, n_max) // boundary * boundary
+    jumps = [(c, ms[i], ms[i + 1]) for i, c in enumerate(counts[:-1]) if c % boundary == 0 and counts[i + 1] == c + after]
+    flat = [ms[i + 1] / ms[i] - 1.0 for i, c in enumerate(counts[:-1]) if c % boundary == after and c > after and counts[i + 1] == c - after + boundary]
+    tile = s.E_local * ctx.moe_tile_rows()   # tokens per GPU at which every expert gets one more row tile
+    big = [b / a - 1.0 for c, a, b in jumps if c % tile == 0]
+    rel = [b / a - 1.0 for c, a, b in jumps if c % tile != 0]
+    cost, sweep = curve.profiling_cost_ms(args.profile_iters), curve.full_sweep_cost_ms(args.profile_iters)
+    log(f"profile: {len(counts)} token counts x {args.profile_iters} launches in {wall:.1f} s wall; "
+        f"kernel time {cost / 1e3:.2f} s vs {sweep / 1e3:.0f} s for a sweep of every count 1..{n_max} ({sweep / cost:.0f}x)")
+    log(f"profile: latency jump when a row-tile boundary is crossed (n = m*{tile} -> +{after}): "
+        + ", ".join(f"{100 * v:.1f} %" for v in big))
+    log(f"profile: latency jump when a 32-row boundary is crossed (n = m*{boundary} -> +{after}): median {100 * sorted(rel)[len(rel) // 2]:.1f} %; "
+        f"change across the rest of a step (m*{boundary}+{after} -> (m+1)*{boundary}): median {100 * sorted(flat)[len(flat) // 2]:.1f} %")
+    for n in (1, boundary, boundary + after, 1024, 4096, 8192, dense_max, n_max):
+        log(f"   C_g({n}) = {curve.at(n):.3f} ms")
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "cg_curve.json"), "w") as fh:
+        json.dump({"boundary": boundary, "after": after, "dense_end": dense_end, "iters": args.profile_iters,
+                   "counts": counts, "ms": ms, "profiling_kernel_ms": cost, "full_sweep_kernel_ms": sweep}, fh)
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,6 +178,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for HBM byte counters)")
+    ap.add_argument("--profile-curve", action="store_true",
+                    help="also run the tile-boundary latency profiler (C_g(n) of the isolated expert kernels)")
+    ap.add_argument("--profile-iters", type=int, default=10)
     ap.add_argument("--curve", action="store_true")
     ap.add_argument("--curve-loads", default="512,1024,2048,4096,8192")
     ap.add_argument("--curve-steps", type=int, default=20)
@@ -214,6 +257,8 @@ def main():
         del src, dst
     if args.curve:
         run_curve(moe, gu, packed, args)
+    if args.profile_curve:
+        run_profile_curve(moe, s, packed, args)
     ctx.close()
     print(json.dumps(result), flush=True)
 

@@ -67,7 +67,7 @@ size_t moe_workspace_bytes(const moe_shape* shape /* host */);
 
 /* Creates a context over a caller-owned device workspace of at least moe_workspace_bytes().
  * The workspace must stay valid until moe_destroy.  Must be called with the target device
- * current.  *ctx is NULL on error. */
+ * current; clears a few KB of the workspace with a blocking memset.  *ctx is NULL on error. */
 moe_status moe_create(moe_ctx** ctx, const moe_shape* shape /* host */, void* workspace,
                       size_t workspace_bytes);
 void moe_destroy(moe_ctx* ctx);
@@ -151,6 +151,20 @@ moe_status moe_stage_times(moe_ctx* ctx, float* ms /* host */);
  * steps of 32 rows, which sets the staircase of the latency-vs-load curve (the
  * paper's tile boundaries, Sec. 3.3.2). */
 int32_t moe_tile_rows(const moe_ctx* ctx);
+
+/* Variability-profiling microbenchmark (paper Sec. 3.3.2, "Step-2"): launches the isolated expert
+ * kernels (moe_grouped_ffn: GEMM1 + SwiGLU + GEMM2) on synthetic rows at each target token count
+ * and records the average latency -- one sample of this GPU's token-vs-latency curve C_g(n) per
+ * count.  For point i, token_counts[i] rows of xp are spread evenly over the E_local resident
+ * experts (the first token_counts[i] % E_local experts get one more), the kernels are launched
+ * warmup + iters times on `stream`, and ms[i] = mean milliseconds per launch over the timed ones
+ * (HIP events on `stream`).  xp and y: device, at least max(token_counts) rows of d bf16 values each;
+ * token_counts and ms: host, n_points entries; every count <= moe_rows_capacity(shape, T_max).
+ * Unlike the hot-path calls this one BLOCKS until the measurements are done, and it overwrites the
+ * context's offsets scratch. */
+moe_status moe_profile_ffn(moe_ctx* ctx, const void* xp, const void* packed, void* y,
+                           const int32_t* token_counts /* host */, int32_t n_points, int32_t warmup,
+                           int32_t iters, float* ms /* host */, void* stream);
 
 /* Tuning hook: force the token-tile class of the expert GEMMs (0: row tiles of up to 128 rows, the
  * low-load class; 1: up to 256 rows, the main class; higher values select alternative kernels kept

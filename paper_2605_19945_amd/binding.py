@@ -55,6 +55,7 @@ _SIGNATURES = {
     "moe_combine": (C.c_int, [_VP, _VP, _VP, _VP, _I32, _VP, _VP]),
     "moe_layer_forward": (C.c_int, [_VP, _VP, _VP, _VP, _VP, _I32, _VP, _VP, _VP]),
     "moe_stage_times": (C.c_int, [_VP, C.POINTER(C.c_float)]),
+    "moe_profile_ffn": (C.c_int, [_VP, _VP, _VP, _VP, C.POINTER(_I32), _I32, _I32, _I32, C.POINTER(C.c_float), _VP]),
     "moe_tile_rows": (_I32, [_VP]),
     "moe_set_tile_class": (C.c_int, [_VP, _I32]),
     "moe_layer_intermediates": (C.c_int, [_VP, C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP)]),
@@ -211,6 +212,18 @@ class MoEContext:
         ms = (C.c_float * len(STAGE_NAMES))()
         self._check(self.lib.moe_stage_times(self._ctx, ms), "moe_stage_times")
         return dict(zip(STAGE_NAMES, (float(v) for v in ms)))
+
+    def moe_profile_ffn(self, xp, packed, token_counts, warmup=3, iters=20, y=None):
+        """Mean milliseconds of the isolated expert kernels at each token count (blocking)."""
+        import torch
+        counts = [int(n) for n in token_counts]
+        if y is None:
+            y = self._empty((max(max(counts, default=0), 1), self.d), torch.bfloat16)
+        arr = (_I32 * len(counts))(*counts)
+        ms = (C.c_float * len(counts))()
+        self._check(self.lib.moe_profile_ffn(self._ctx, _ptr(xp), _ptr(packed), _ptr(y), arr, len(counts), warmup,
+                                             iters, ms, _stream()), "moe_profile_ffn")
+        return [float(v) for v in ms]
 
     def moe_tile_rows(self):
         return int(self.lib.moe_tile_rows(self._ctx))

@@ -303,6 +303,54 @@ moe_status moe_grouped_ffn(moe_ctx* c, const void* xp, const int32_t* offsets, i
                    (uint16_t*)y, (hipStream_t)stream, nullptr);
 }
 
+moe_status moe_profile_ffn(moe_ctx* c, const void* xp, const void* packed, void* y, const int32_t* token_counts,
+                           int32_t n_points, int32_t warmup, int32_t iters, float* ms, void* stream) {
+    if (c == nullptr || token_counts == nullptr || ms == nullptr || n_points < 0 || warmup < 0 || iters < 1)
+        return MOE_ERR_INVALID_ARG;
+    if (bad_bf16(xp) || bad_bf16(packed) || bad_bf16(y)) return MOE_ERR_INVALID_ARG;
+    for (int i = 0; i < n_points; ++i)
+        if (token_counts[i] < 0 || token_counts[i] > c->rows_cap) return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const int E_local = c->s.E_local;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (note_hip(hipEventCreate(&e0), "hipEventCreate") != MOE_OK) return MOE_ERR_DEVICE;
+    if (note_hip(hipEventCreate(&e1), "hipEventCreate") != MOE_OK) {
+        (void)hipEventDestroy(e0);
+        return MOE_ERR_DEVICE;
+    }
+    int32_t host_off[257];
+    moe_status rc = MOE_OK;
+    for (int i = 0; i < n_points && rc == MOE_OK; ++i) {
+        const int n = token_counts[i];
+        ms[i] = 0.f;
+        if (n == 0) continue;
+        // n rows spread evenly over the resident experts, the first n % E_local get one more
+        host_off[0] = 0;
+        for (int e = 0; e < E_local; ++e) host_off[e + 1] = host_off[e] + n / E_local + (e < n % E_local ? 1 : 0);
+        rc = note_hip(hipMemcpyAsync(c->offsets, host_off, (size_t)(E_local + 1) * 4, hipMemcpyHostToDevice, st),
+                      "hipMemcpyAsync(offsets)");
+        if (rc != MOE_OK) break;
+        rc = note_hip(hipStreamSynchronize(st), "hipStreamSynchronize");  // host_off is reused
+        if (rc != MOE_OK) break;
+        const int cls = c->forced_cls >= 0 ? c->forced_cls : gemm_pick_class((double)n / E_local);
+        for (int r = 0; r < warmup + iters && rc == MOE_OK; ++r) {
+            if (r == warmup) rc = note_hip(hipEventRecord(e0, st), "hipEventRecord");
+            if (rc == MOE_OK)
+                rc = run_ffn(c, cls, (const uint16_t*)xp, nullptr, c->offsets, n, (const uint16_t*)packed,
+                             (uint16_t*)y, st, nullptr);
+        }
+        if (rc != MOE_OK) break;
+        rc = note_hip(hipEventRecord(e1, st), "hipEventRecord");
+        if (rc == MOE_OK) rc = note_hip(hipEventSynchronize(e1), "hipEventSynchronize");
+        float t = 0.f;
+        if (rc == MOE_OK) rc = note_hip(hipEventElapsedTime(&t, e0, e1), "hipEventElapsedTime");
+        ms[i] = t / (float)iters;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
+
 moe_status moe_combine(moe_ctx* c, const void* y, const int32_t* row_of, const float* topk_w, int32_t T,
                        void* out, void* stream) {
     if (c == nullptr || T < 0 || T > c->s.T_max) return MOE_ERR_INVALID_ARG;

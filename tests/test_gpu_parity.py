@@ -378,3 +378,32 @@ def test_error_codes_on_device(moe):
     with pytest.raises(moe.MoEError):
         moe.MoEContext(64, 100, 256, 8, 2)
     ctx.close()
+
+
+def test_profile_ffn_runs_the_same_kernels_as_grouped_ffn(moe):
+    """The variability-profiling microbenchmark: its last launch leaves in y exactly what
+    moe_grouped_ffn computes for the same even split, the latencies are positive and grow with the
+    load, and counts beyond the capacity are rejected."""
+    import torch
+    E_local, d, f, cap = 4, 256, 384, 700
+    W1, W3, W2 = wl.expert_weights(21, E_local, d, f, 0.08)
+    xp = wl.gaussian_bf16_bits(21, 9, (cap, d), 1.0)
+    ctx = moe.MoEContext(cap, d, f, E_local, 1)
+    packed = ctx.moe_pack_weights(gu.to_dev_bf16(W1), gu.to_dev_bf16(W3), gu.to_dev_bf16(W2))
+    xd = gu.to_dev_bf16(xp)
+    counts = [1, 130, 0, 699]
+    y = torch.full((cap, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ms = ctx.moe_profile_ffn(xd, packed, counts, warmup=1, iters=3, y=y)
+    torch.cuda.synchronize()
+    assert len(ms) == 4 and ms[2] == 0.0 and all(m > 0 for m in (ms[0], ms[1], ms[3]))
+    n = counts[-1]
+    off = np.zeros(E_local + 1, dtype=np.int32)
+    for e in range(E_local):
+        off[e + 1] = off[e] + n // E_local + (1 if e < n % E_local else 0)
+    want = ctx.moe_grouped_ffn(xd, gu.to_dev(off), n, packed)
+    torch.cuda.synchronize()
+    assert torch.equal(y[:n].view(torch.int16), want[:n].view(torch.int16))
+    gu.check_output(gu.f64_of_bf16(y[:n]), orc.grouped_ffn(xp[:n], off, W1, W3, W2), what="profile y")
+    with pytest.raises(moe.MoEError):
+        ctx.moe_profile_ffn(xd, packed, [cap + 1])
+    ctx.close()
