@@ -122,8 +122,11 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                 }
             }
         }
-        // ---- pieces: C slots each, C = mean row tiles per loaded expert ----------------------------
-        int C = tot[5] > 0 ? (MT + tot[5] / 2) / tot[5] : 1;
+        // ---- pieces: C slots each.  C = the mean number of row tiles per loaded expert, or, when that
+        //      exceeds SCHED_PIECE_MAX, that mean cut into the fewest equal parts that fit ------------
+        const int En = tot[5] > 0 ? tot[5] : 1;
+        const int parts = (MT + En * SCHED_PIECE_MAX - 1) / (En * SCHED_PIECE_MAX);  // ceil(mean / max)
+        int C = parts <= 1 ? (MT + En / 2) / En : (MT + En * parts - 1) / (En * parts);
         C = C < 1 ? 1 : (C > SCHED_PIECE_MAX ? SCHED_PIECE_MAX : C);
         const int mte_mine = (nblk_e + cap - 1) / cap;
         const int pp_incl = block_scan_incl((mte_mine + C - 1) / C, s_part);
@@ -149,8 +152,11 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                 const int e = lo;
                 const int mte = s_mte[e], pp = s_pre[e + 1] - s_pre[e];
                 const int q = piece - s_pre[e] * nt;
-                const int ni = q / pp, mi = (q % pp) * C + pos;
-                if (mi < mte) {
+                // the expert's row tiles are dealt evenly to its pp pieces per weight-row tile
+                const int ni = q / pp, pc = q % pp;
+                const int pbase = mte / pp, prem = mte % pp;
+                const int mi = pc * pbase + min(pc, prem) + pos;
+                if (pos < pbase + (pc < prem ? 1 : 0)) {
                     const int e_rows = s_off[e + 1] - s_off[e];
                     // 32-row blocks of the expert, dealt evenly to its mte tiles
                     const int nblk = (e_rows + 31) / 32;
