@@ -269,8 +269,7 @@ moe_status moe_permute(moe_ctx* c, const void* x, const int32_t* topk_idx, int32
     hipError_t e = launch_permute(topk_idx, T, c->s.k, c->s.e_lo, c->s.E_local, c->blockhist, offsets, row_of,
                                   tok_of, st);
     if (e == hipSuccess && xp != nullptr)
-        e = launch_gather((const uint16_t*)x, tok_of, offsets, c->s.E_local, moe_rows_capacity(&c->s, T),
-                          c->s.d, (uint16_t*)xp, st);
+        e = launch_gather((const uint16_t*)x, row_of, T, c->s.k, c->s.d, (uint16_t*)xp, st);
     return from_hip(e);
 }
 

@@ -92,8 +92,8 @@ hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias
                         TileDesc* table_ws, int32_t* route_ws, hipStream_t st);
 hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
                           int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st);
-hipError_t launch_gather(const uint16_t* x, const int32_t* tok_of, const int32_t* offsets, int E_local,
-                         int64_t rows_cap, int d, uint16_t* xp, hipStream_t st);
+hipError_t launch_gather(const uint16_t* x, const int32_t* row_of, int T, int k, int d, uint16_t* xp,
+                         hipStream_t st);
 hipError_t launch_combine(const uint16_t* y, const int32_t* row_of, const float* w, int T, int k, int d,
                           uint16_t* out, hipStream_t st);
 

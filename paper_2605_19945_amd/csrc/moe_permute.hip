@@ -9,7 +9,7 @@
 //   2. one workgroup: exclusive scan over blocks (per expert) and over experts -> offsets,
 //   3. per block: rank of every assignment among the block's earlier tokens, from per-wavefront
 //      64-bit membership masks in LDS -> row_of, tok_of.
-// The row copy itself (xp[row] = x[tok_of[row]]) is a separate streaming kernel.
+// The row copy itself (xp[row_of[t, j]] = x[t]) is a separate streaming kernel.
 #include "moe_internal.h"
 
 constexpr int PB = 256;  // tokens per block (one token per thread)
@@ -110,29 +110,45 @@ hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_loca
     return hipGetLastError();
 }
 
-// xp[r, :] = x[tok_of[r], :] for r < offsets[E_local]; 16 bytes per lane, one wavefront per row
-// segment of 1 KiB, grid-stride over rows so the launch does not depend on the device-side count.
-__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x,
-                                                          const int32_t* __restrict__ tok_of,
-                                                          const int32_t* __restrict__ offsets, int E_local,
-                                                          int chunks /* d / 8 */, uint4* __restrict__ xp) {
-    const int n_rows = offsets[E_local];
-    const int rows_per_block = blockDim.x / 64 * 1;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int r = blockIdx.x * rows_per_block + wave; r < n_rows; r += gridDim.x * rows_per_block) {
-        const uint4* src = x + (size_t)tok_of[r] * chunks;
-        uint4* dst = xp + (size_t)r * chunks;
-        for (int c = lane; c < chunks; c += 64) dst[c] = src[c];
+// xp[row_of[t, j], :] = x[t, :] for every local assignment: one wavefront per token reads the row once
+// (16 bytes per lane, four chunks in flight) and stores it to its up-to-k destination rows; rows of xp
+// that no assignment maps to are left untouched.  Grid-stride over tokens.
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restrict__ x,
+                                                           const int32_t* __restrict__ row_of, int T, int k,
+                                                           int chunks /* d / 8 */, uint4* __restrict__ xp) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int t = blockIdx.x * 4 + wave; t < T; t += gridDim.x * 4) {
+        const uint4* src = x + (size_t)t * chunks;
+        const int32_t* dst_rows = row_of + (size_t)t * k;
+        for (int c0 = 0; c0 < chunks; c0 += 256) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < chunks) v[u] = src[c];
+            }
+            for (int j = 0; j < k; ++j) {
+                const int r = dst_rows[j];
+                if (r < 0) continue;  // expert not resident (wave-uniform)
+                uint4* dst = xp + (size_t)r * chunks;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u * 64 + lane;
+                    if (c < chunks) dst[c] = v[u];
+                }
+            }
+        }
     }
 }
 
-hipError_t launch_gather(const uint16_t* x, const int32_t* tok_of, const int32_t* offsets, int E_local,
-                         int64_t rows_cap, int d, uint16_t* xp, hipStream_t st) {
-    int64_t blocks = (rows_cap + 3) / 4;
-    if (blocks > 8192) blocks = 8192;
+hipError_t launch_gather(const uint16_t* x, const int32_t* row_of, int T, int k, int d, uint16_t* xp,
+                         hipStream_t st) {
+    int blocks = (T + 3) / 4;
+    if (blocks > 16384) blocks = 16384;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(gather_rows_kernel, dim3((int)blocks), dim3(256), 0, st, (const uint4*)x, tok_of,
-                       offsets, E_local, d / 8, (uint4*)xp);
+    hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks), dim3(256), 0, st, (const uint4*)x, row_of, T, k, d / 8,
+                       (uint4*)xp);
     return hipGetLastError();
 }
 
