@@ -155,12 +155,13 @@ class MoEContext:
         return packed
 
     # ---- hot path ------------------------------------------------------------------------------
-    def moe_route(self, x, router_packed, bias=None, T=None):
+    def moe_route(self, x, router_packed, bias=None, T=None, idx=None, w=None, counts=None):
+        """idx / w / counts: optional caller-provided outputs (e.g. one row of a trace matrix)."""
         import torch
         T = x.shape[0] if T is None else T
-        idx = self._empty((T, self.k), torch.int32)
-        w = self._empty((T, self.k), torch.float32)
-        counts = self._empty((self.E,), torch.int32)
+        idx = self._empty((T, self.k), torch.int32) if idx is None else idx
+        w = self._empty((T, self.k), torch.float32) if w is None else w
+        counts = self._empty((self.E,), torch.int32) if counts is None else counts
         if T == 0:
             counts.zero_()
         self._check(self.lib.moe_route(self._ctx, _ptr(x), _ptr(router_packed), _ptr(bias), T, _ptr(idx), _ptr(w),

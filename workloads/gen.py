@@ -27,6 +27,7 @@ _THREADS = 8
 
 # tensor ids (second word of the seed sequence)
 _TID_X, _TID_WG, _TID_BIAS, _TID_W1, _TID_W3, _TID_W2, _TID_DIR, _TID_GROUPS, _TID_XP = range(1, 10)
+_TID_STEPS = 10
 
 
 @dataclass(frozen=True)
@@ -239,3 +240,38 @@ def ep_share_groups(N: int, seed: int = 0, d=EP_D, E_local=EP_ELOCAL, zipf_s: fl
     offsets[1:] = np.cumsum(n_e)
     xp = gaussian_bf16_bits(seed, _TID_XP, (N, d), 1.0)
     return xp, offsets
+
+
+TRACE_CONSISTENT = (1, 6)     # lead the router in every step
+TRACE_PAIR = (2, 5)           # correlated temporal experts: heavily used together in a few steps
+TRACE_ACTIVE_FRACTION = 0.17  # share of the steps in which the pair is active
+TRACE_BURST_TOKENS = 0.6      # share of a step's tokens whose top-2 is the pair when it is active
+
+
+def trace_steps(S: int = 16, T: int = 256, seed: int = 0, d: int = 512, E: int = 8, k: int = 2):
+    """S consecutive time steps of one router (the structure the paper describes for expert
+    utilisation over time): two consistent experts lead in every step; a pair of temporal experts is
+    active together in about 17 % of the steps (at least two of them, never the first), where it takes
+    the top-2 of 60 % of that step's tokens.  Returns (list of S routing-only MoEInputs sharing Wg and
+    bias, list of S booleans: pair active)."""
+    s = MoEShape(T, d, 64, E, k)
+    Wg = gaussian_f32(seed, _TID_WG, (d, E), 1.0 / math.sqrt(d))
+    bias = np.zeros(E, dtype=np.float32)
+    for e in TRACE_CONSISTENT:
+        bias[e] = 1.5
+    u = gaussian_f32(seed, _TID_DIR, (1, d), 1.0)[0].astype(np.float64)
+    u /= np.sqrt((u * u).sum())
+    for e in TRACE_PAIR:
+        Wg[:, e] += (SKEW_BETA * u).astype(np.float32)
+    g = np.random.Generator(np.random.SFC64(np.random.SeedSequence([seed, _TID_STEPS, S])))
+    n_active = max(2, int(round(TRACE_ACTIVE_FRACTION * S)))
+    active_steps = set((1 + g.permutation(S - 1)[:n_active]).tolist()) if S > 2 else set()
+    steps, active = [], []
+    for t in range(S):
+        xf = gaussian_f32(seed + 1000 * (t + 1), _TID_X, (T, d), 1.0)
+        on = t in active_steps
+        if on:
+            xf[: int(round(TRACE_BURST_TOKENS * T))] += (SKEW_ALPHA * u).astype(np.float32)
+        steps.append(MoEInputs(f"trace_step{t}", s, bf16_bits_from_f32(xf), Wg, bias))
+        active.append(on)
+    return steps, active
