@@ -166,6 +166,52 @@ def run_profile_curve(moe, s, packed, args):
     ctx.close()
 
 
+def run_gem_demo(moe, gu, s, packed, args):
+    """The paper's pipeline end to end on one GPU: Step-2 profile of the expert kernels at E/G experts
+    per GPU, Step-1 trace of S router steps, Step-3 mapping search.  GPU-to-GPU variability is emulated
+    as in the paper's sensitivity study (Sec. 5): G copies of the measured curve, the last one 12 % slower."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_2605_19945_amd import latency_curve as lc, trace as tr
+    G, S, T = 4, 16, 2048
+    per_gpu = s.E // G
+    # Step-2: curve of one GPU holding per_gpu experts
+    ctx = moe.MoEContext(S * 0 + 4 * T * s.k, s.d, s.f, per_gpu, 1)
+    n_max = ctx.rows_capacity(4 * T * s.k)
+    counts = lc.sample_counts(per_gpu * 32, min(n_max, per_gpu * 2048), n_max, 2048, per_gpu)
+    xp = torch.randn(n_max, s.d, device="cuda").bfloat16()
+    sub = packed[: ctx.lib.moe_packed_weight_bytes(__import__("ctypes").byref(ctx.shape)) // 2]
+    ms = ctx.moe_profile_ffn(xp, sub, counts, warmup=2, iters=args.profile_iters)
+    ctx.close()
+    curves = [(counts, [m * (1.12 if g == G - 1 else 1.0) for m in ms]) for g in range(G)]
+    # Step-1: trace of S steps through the router on the GPU
+    steps, active = wl.trace_steps(S, T, args.seed, d=s.d, E=s.E, k=s.k)
+    rctx = moe.MoEContext(T, s.d, 64, s.E, s.k)
+    rp = rctx.moe_pack_router(gu.to_dev(steps[0].Wg))
+    bias = gu.to_dev(steps[0].bias)
+    trace_dev = torch.zeros(S, s.E, dtype=torch.int32, device="cuda")
+    for t, inp in enumerate(steps):
+        rctx.moe_route(gu.to_dev_bf16(inp.x), rp, bias, counts=trace_dev[t])
+    torch.cuda.synchronize()
+    trace = trace_dev.cpu().numpy()
+    rctx.close()
+    # Step-3: mapping search (30 restarts, noise drawn here and handed in)
+    K = 30
+    noise = np.random.default_rng(args.seed).uniform(-1.0, 1.0, (K, s.E)).astype(np.float32)
+    t0 = time.perf_counter()
+    M, score, swaps = moe.moe_gem_place(trace, curves, noise, K)
+    dt = time.perf_counter() - t0
+    linear = [e // per_gpu for e in range(s.E)]
+    s_lin = moe.moe_gem_score(trace, curves, linear)
+    a, b = wl.TRACE_PAIR
+    log(f"gem-demo: {S}-step trace, mean utilisation {tr.mean_utilisation(trace).round(0).tolist()}, "
+        f"pair {wl.TRACE_PAIR} r = {tr.pearson(trace, a, b):.2f}, active steps {[t for t in range(S) if active[t]]}")
+    log(f"gem-demo: C_g sampled at {len(counts)} counts; GPU {G - 1} emulated 12 % slower")
+    log(f"gem-demo: linear mapping {linear} score {s_lin:.3f} ms; searched mapping {M.tolist()} score {score:.3f} ms "
+        f"({100 * (1 - score / s_lin):.1f} % lower predicted straggler latency; {swaps} swaps; search {dt * 1e3:.1f} ms)")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -181,6 +227,8 @@ def main():
     ap.add_argument("--profile-curve", action="store_true",
                     help="also run the tile-boundary latency profiler (C_g(n) of the isolated expert kernels)")
     ap.add_argument("--profile-iters", type=int, default=10)
+    ap.add_argument("--gem-demo", action="store_true",
+                    help="profile -> trace -> mapping search on emulated GPU variability (paper Steps 1-3)")
     ap.add_argument("--curve", action="store_true")
     ap.add_argument("--curve-loads", default="512,1024,2048,4096,8192")
     ap.add_argument("--curve-steps", type=int, default=20)
@@ -259,6 +307,8 @@ def main():
         run_curve(moe, gu, packed, args)
     if args.profile_curve:
         run_profile_curve(moe, s, packed, args)
+    if args.gem_demo:
+        run_gem_demo(moe, gu, s, packed, args)
     ctx.close()
     print(json.dumps(result), flush=True)
 

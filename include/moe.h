@@ -166,6 +166,31 @@ moe_status moe_profile_ffn(moe_ctx* ctx, const void* xp, const void* packed, voi
                            const int32_t* token_counts /* host */, int32_t n_points, int32_t warmup,
                            int32_t iters, float* ms /* host */, void* stream);
 
+/* ---- host-side mapping search (paper Sec. 3.3.3 "Step-3", Eq. 1; appendix Alg. "Initialmapping",
+ * "Refine", "Place").  Everything here is HOST memory and runs on the CPU, as in the paper; the
+ * inputs are what the GPU path produces: trace[t*E + e] = tokens routed to expert e at step t (the
+ * counts_out rows of S consecutive calls) and one token-vs-latency curve per GPU (moe_profile_ffn
+ * samples): GPU g's samples are curve_counts / curve_ms [curve_offsets[g], curve_offsets[g+1]),
+ * token counts strictly ascending; C_g(n) joins neighbouring samples by straight lines (first
+ * sample's value below it, last one's above it, 0 for n <= 0).  E must be a multiple of G: every
+ * GPU hosts E / G experts.  mapping[e] = GPU of expert e. -------------------------------------- */
+
+/* S(M) = sum over steps of max over GPUs of C_g(tokens routed to GPU g at that step)  (Eq. 1). */
+moe_status moe_gem_score(const int32_t* trace, int32_t S, int32_t E, int32_t G, const int32_t* curve_counts,
+                         const float* curve_ms, const int32_t* curve_offsets /* [G+1] */,
+                         const int32_t* mapping /* [E] */, double* score_out);
+
+/* K restarts of: greedy initial mapping (experts by mean utilisation, heaviest first, each on the
+ * GPU with a free slot that gives the lowest score of the partial mapping; restart i > 0 sorts by
+ * u_e * (1 + 0.2 * noise[i*E + e]), noise in [-1, 1) drawn by the caller), then repeated best
+ * cross-GPU swap until the best swap lowers the score by less than 0.1 %.  Returns the
+ * lowest-scoring mapping, its score and (optionally) the number of swaps its refinement took.
+ * noise may be NULL when K == 1.  Ties go to the lower expert / GPU index and the first pair. */
+moe_status moe_gem_place(const int32_t* trace, int32_t S, int32_t E, int32_t G, const int32_t* curve_counts,
+                         const float* curve_ms, const int32_t* curve_offsets /* [G+1] */,
+                         const float* noise /* [K][E] */, int32_t K, int32_t* mapping_out /* [E] */,
+                         double* score_out, int32_t* swaps_out /* or NULL */);
+
 /* Tuning hook: force the token-tile class of the expert GEMMs (0: row tiles of up to 128 rows, the
  * low-load class; 1: up to 256 rows, the main class; higher values select alternative kernels kept
  * for tuning runs; -1: choose from the expected rows per expert, the default). */

@@ -11,4 +11,6 @@ from .binding import (  # noqa: F401
     exported_symbols,
     STAGE_NAMES,
     FLAG_STAGE_EVENTS,
+    moe_gem_score,
+    moe_gem_place,
 )

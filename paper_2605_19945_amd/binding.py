@@ -56,6 +56,9 @@ _SIGNATURES = {
     "moe_layer_forward": (C.c_int, [_VP, _VP, _VP, _VP, _VP, _I32, _VP, _VP, _VP]),
     "moe_stage_times": (C.c_int, [_VP, C.POINTER(C.c_float)]),
     "moe_profile_ffn": (C.c_int, [_VP, _VP, _VP, _VP, C.POINTER(_I32), _I32, _I32, _I32, C.POINTER(C.c_float), _VP]),
+    "moe_gem_score": (C.c_int, [_VP, _I32, _I32, _I32, _VP, _VP, _VP, _VP, C.POINTER(C.c_double)]),
+    "moe_gem_place": (C.c_int, [_VP, _I32, _I32, _I32, _VP, _VP, _VP, _VP, _I32, _VP, C.POINTER(C.c_double),
+                                C.POINTER(_I32)]),
     "moe_tile_rows": (_I32, [_VP]),
     "moe_set_tile_class": (C.c_int, [_VP, _I32]),
     "moe_layer_intermediates": (C.c_int, [_VP, C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP)]),
@@ -246,3 +249,45 @@ class MoEContext:
         A = T * self.k
         return (view(p[0], A, torch.int32).view(T, self.k), view(p[1], A, torch.float32).view(T, self.k),
                 view(p[2], self.E_local + 1, torch.int32), view(p[3], A, torch.int32).view(T, self.k))
+
+
+# ---- host-side mapping search (no context, no GPU) ------------------------------------------------
+def _curve_arrays(curves):
+    import numpy as np
+    counts = np.concatenate([np.asarray(c, dtype=np.int32) for c, _ in curves])
+    ms = np.concatenate([np.asarray(m, dtype=np.float32) for _, m in curves])
+    off = np.zeros(len(curves) + 1, dtype=np.int32)
+    off[1:] = np.cumsum([len(c) for c, _ in curves])
+    return counts, ms, off
+
+
+def moe_gem_score(trace, curves, mapping):
+    """Eq. 1 score of `mapping` (GPU of each expert); trace [S][E] ints; curves: per GPU (counts, ms)."""
+    import numpy as np
+    lib = load_library()
+    t = np.ascontiguousarray(trace, dtype=np.int32)
+    counts, ms, off = _curve_arrays(curves)
+    m = np.ascontiguousarray(mapping, dtype=np.int32)
+    out = C.c_double()
+    st = lib.moe_gem_score(t.ctypes.data, t.shape[0], t.shape[1], len(curves), counts.ctypes.data, ms.ctypes.data,
+                           off.ctypes.data, m.ctypes.data, C.byref(out))
+    if st != 0:
+        raise MoEError(st, "moe_gem_score")
+    return out.value
+
+
+def moe_gem_place(trace, curves, noise=None, K=1):
+    """The paper's mapping search; returns (mapping [E], score, swaps of the winning restart)."""
+    import numpy as np
+    lib = load_library()
+    t = np.ascontiguousarray(trace, dtype=np.int32)
+    counts, ms, off = _curve_arrays(curves)
+    nz = np.ascontiguousarray(noise, dtype=np.float32) if noise is not None else None
+    mapping = np.zeros(t.shape[1], dtype=np.int32)
+    score, swaps = C.c_double(), _I32()
+    st = lib.moe_gem_place(t.ctypes.data, t.shape[0], t.shape[1], len(curves), counts.ctypes.data, ms.ctypes.data,
+                           off.ctypes.data, nz.ctypes.data if nz is not None else None, K, mapping.ctypes.data,
+                           C.byref(score), C.byref(swaps))
+    if st != 0:
+        raise MoEError(st, "moe_gem_place")
+    return mapping, score.value, swaps.value
