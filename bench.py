@@ -40,6 +40,10 @@ def make_workload(name, seed, weights):
         return wl.fine_grained(int(name.split("T")[-1]), seed, weights=weights)
     if name.startswith("ep_share_T"):
         return wl.ep_share_layer(int(name.split("T")[-1]), seed, weights=weights)
+    if name.startswith("wide_few_T"):
+        return wl.wide_few_experts(int(name.split("T")[-1]), seed, weights=weights)
+    if name.startswith("mid_grained_T"):
+        return wl.mid_grained(int(name.split("T")[-1]), seed, weights=weights)
     if name == "tiny":
         return wl.tiny(seed)
     raise SystemExit(f"unknown workload {name}")

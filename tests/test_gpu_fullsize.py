@@ -107,6 +107,18 @@ def test_fine_grained_T8192_layer(moe):
     run_full_layer(moe, wl.fine_grained(8192, 0, weights=weights), n_random=128)
 
 
+def test_wide_few_experts_layer(moe):
+    """16 wide experts, top-1 (second shape family; d = 5120 takes the generic small-router kernel)."""
+    weights = weights_for("wide", 16, 5120, 8192)
+    run_full_layer(moe, wl.wide_few_experts(4096, 0, weights=weights), n_random=96)
+
+
+def test_mid_grained_layer(moe):
+    """64 medium experts, top-8 (third shape family; router logits on the split-K GEMM path)."""
+    weights = weights_for("mid", 64, 4096, 3072)
+    run_full_layer(moe, wl.mid_grained(4096, 0, weights=weights), n_random=96)
+
+
 @pytest.mark.parametrize("T", [128, 2048])
 def test_ep_share_layer(moe, T):
     weights = weights_for("ep", wl.EP_ELOCAL, wl.EP_D, wl.EP_F)

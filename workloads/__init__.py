@@ -20,6 +20,8 @@ from .gen import (  # noqa: F401
     ep_share_groups,
     custom,
     trace_steps,
+    wide_few_experts,
+    mid_grained,
     TRACE_CONSISTENT, TRACE_PAIR,
     MIXTRAL_D, MIXTRAL_F, MIXTRAL_E, MIXTRAL_K,
     EP_D, EP_F, EP_E, EP_K, EP_ELO, EP_ELOCAL,

@@ -275,3 +275,23 @@ def trace_steps(S: int = 16, T: int = 256, seed: int = 0, d: int = 512, E: int =
         steps.append(MoEInputs(f"trace_step{t}", s, bf16_bits_from_f32(xf), Wg, bias))
         active.append(on)
     return steps, active
+
+
+def wide_few_experts(T: int = 8192, seed: int = 0, weights=None) -> MoEInputs:
+    """A second shape family: few wide experts, top-1 (d=5120, f=8192, E=16, k=1 -- the proportions of
+    the 16-expert model the paper evaluates; its exact dimensions are not in the paper)."""
+    s = MoEShape(T, 5120, 8192, 16, 1)
+    x = gaussian_bf16_bits(seed, _TID_X, (T, s.d), 1.0)
+    Wg = gaussian_f32(seed, _TID_WG, (s.d, s.E), 1.0 / math.sqrt(s.d))
+    bias = gaussian_f32(seed, _TID_BIAS, (s.E,), 0.5)
+    return _attach_weights(MoEInputs(f"wide_few_T{T}", s, x, Wg, bias), seed, weights)
+
+
+def mid_grained(T: int = 8192, seed: int = 0, weights=None) -> MoEInputs:
+    """A third shape family: 64 medium experts, top-8 (d=4096, f=3072, E=64, k=8 -- the proportions of
+    the 64-expert model the paper evaluates; its exact dimensions are not in the paper)."""
+    s = MoEShape(T, 4096, 3072, 64, 8)
+    x = gaussian_bf16_bits(seed, _TID_X, (T, s.d), 1.0)
+    Wg = gaussian_f32(seed, _TID_WG, (s.d, s.E), 1.0 / math.sqrt(s.d))
+    bias = gaussian_f32(seed, _TID_BIAS, (s.E,), 0.5)
+    return _attach_weights(MoEInputs(f"mid_grained_T{T}", s, x, Wg, bias), seed, weights)
