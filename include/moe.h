@@ -192,7 +192,7 @@ moe_status moe_gem_place(const int32_t* trace, int32_t S, int32_t E, int32_t G, 
                          double* score_out, int32_t* swaps_out /* or NULL */);
 
 /* Tuning hook: force the token-tile class of the expert GEMMs (0: row tiles of up to 128 rows, the
- * low-load class; 1: up to 256 rows, the main class; higher values select alternative kernels kept
+ * low-load class; 1: up to 288 rows, the main class; higher values select alternative kernels kept
  * for tuning runs; -1: choose from the expected rows per expert, the default). */
 moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
 

@@ -1,7 +1,5 @@
 // Work list, tile classes, plans and launches of the grouped GEMMs (the kernel itself lives in
 // moe_gemm_kernel.h and is instantiated per epilogue in moe_gemm_{swiglu,plain,pairsum}.hip).
-#include <stdlib.h>
-
 #include "moe_internal.h"
 
 // ------------------------------------------------------------------------------------------------
@@ -16,25 +14,35 @@
 // Sec. 3.3.2, seen from the scheduler's side.  Estimated time of a cap, in units of one 32-row
 // block of MFMA work: rounds * (mean tile height in blocks + SCHED_TILE_OVERHEAD).
 //
-// XCD-aware order.  Workgroup b runs on XCD b % 8.  A "piece" is C consecutive slots for row tiles of
-// one expert and one weight-row tile (they share that weight panel); C is the mean number of row
-// tiles per loaded expert (1..8), an expert with fewer row tiles leaves the last slots of its piece
-// empty, one with more has several pieces per weight-row tile.  Pieces are numbered expert-major,
-// then weight-row tile, and dealt round-robin to the XCDs.  So the workgroups resident on one XCD at
-// a time are a few consecutive weight-row tiles of one expert times its row tiles: a weight panel
-// is fetched into one L2 (one per piece), the token panels are shared by the pieces running side by
-// side, and every XCD gets the same number of slots.  Empty slots cost one workgroup that exits at
-// once; they number fewer than the row tiles.
+// Order of the work list.  The hardware hands out the workgroups of a launch in index order:
+// workgroup b goes to XCD b % 8, and within an XCD to shader engine (b / 8) % 4, whose eight compute
+// units take whatever arrives there; the XCD's dispatcher does not move on while the engine whose
+// turn it is has no free compute unit (measured with per-workgroup time stamps: an engine that
+// keeps receiving workgroups with nothing to do idles, it cannot run ahead of the other three).
+// So each XCD's queue -- the entries b = x, x + 8, x + 16, ... of the table -- is dense: real tiles
+// only, empty entries follow after the last one.
+//
+// A "piece" is up to SCHED_PIECE_MAX row tiles of one expert and one weight-row tile, consecutive in
+// one XCD's queue: they run side by side and share that weight panel in the XCD's L2.  An expert
+// with more row tiles has pp > 1 pieces per weight-row tile, as equal as possible (the first
+// mte % pp one tile longer).  Pieces are numbered expert-major, then weight-row tile, then piece,
+// and dealt round-robin to the XCDs; pp is odd (or every piece is a single tile), so every XCD meets
+// the longer and the shorter pieces of an expert in turn.  The workgroups resident on one XCD at a
+// time are then a few consecutive weight-row tiles of one expert times its row tiles, and the token
+// panels are shared by the pieces running side by side.  With few work items the pieces are made
+// shorter so that there are at least 64 of them.
 // ------------------------------------------------------------------------------------------------
 constexpr int SCHED_CU = 256;    // compute units of the device (one workgroup each)
-constexpr int SCHED_PIECE_MAX = 8;  // slots per piece, at most
+constexpr int SCHED_PIECE_MAX = 8;  // row tiles per piece, at most
 // Per-tile cost that does not scale with the tile's height, in 32-row blocks of MFMA work: every
 // tile streams its whole 256-row weight panel whatever its height.  Fitted to measured launch times
 // of the Mixtral-shape GEMMs at caps of 192 and 256 rows (tile time ~ blocks + 3.4).
 constexpr float SCHED_TILE_OVERHEAD = 3.5f;
 static __host__ __device__ inline int sched_min_cap_blocks(int bm) { return (5 * (bm / 32) + 7) / 8; }
-// upper bound on the slots of a launch: padded row tiles < 2 * row tiles, rounded up to whole rounds
-// of 8 pieces
+// Entries of a work list (= workgroups of the launch): eight times the longest XCD queue must fit.
+// The queues together hold (row tiles * weight-row tiles) entries; dealing whole pieces can leave them
+// unequal, and the scheduler falls back to single-tile pieces, whose queues differ by at most one
+// entry, when the longest one would not fit.
 static inline int sched_grid(int mt_max, int nt) { return 2 * mt_max * nt + 8 * SCHED_PIECE_MAX; }
 
 // inclusive prefix sum over the 64 lanes with data-parallel-primitive moves: a Kogge-Stone scan inside
@@ -62,16 +70,30 @@ static __device__ inline int block_scan_incl(int v, int32_t* part) {
     return v;
 }
 
+// Tiles in the first i pieces that one XCD holds of an expert: the pieces q0, q0 + 8, q0 + 16, ... of
+// its pp * nt pieces, piece q being the (q % pp)-th of a weight-row tile.  mte row tiles in pp pieces.
+static __device__ inline int sched_tiles_before(int i, int q0, int mte, int pp) {
+    const int pbase = mte / pp, prem = mte % pp;
+    const int full = i / pp, m = i % pp;  // pp consecutive visits meet every piece number once
+    int t = full * mte + m * pbase;
+    if (prem)
+        for (int k = 0; k < m; ++k) t += ((q0 + 8 * k) % pp) < prem ? 1 : 0;
+    return t;
+}
+
 __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict__ offsets, int E_local,
                                                        int bm, int bn, int nt1, int grid1,
                                                        TileDesc* __restrict__ t1, int nt2, int grid2,
                                                        TileDesc* __restrict__ t2, int host_rows) {
     __shared__ int32_t s_off[257];
-    __shared__ int32_t s_mte[256];   // row tiles of expert e
-    __shared__ int32_t s_pre[257];   // pieces per weight-row tile of the experts before e; [E_local] = total
+    __shared__ int32_t s_mte[256];     // row tiles of expert e
+    __shared__ int32_t s_pre[257];     // pieces per weight-row tile of the experts before e; [E_local] = total
+    __shared__ int32_t s_len[8][257];  // tiles in XCD x's queue before those of expert e; [E_local] = length
+    __shared__ int32_t s_wave[8][4];
     __shared__ int32_t s_part[4];
     __shared__ int32_t s_tot[6][4];
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     // host_rows >= 0: one group of host_rows rows (the router GEMM), no offsets array to read
     int nblk_e = 0;  // 32-row blocks of expert tid
     if (tid < E_local) {
@@ -90,7 +112,6 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
         tot[c + 1] = (h >= hmin && nblk_e > 0) ? (nblk_e + h - 1) / h : 0;
     }
     {
-        const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
         for (int c = 0; c < 6; ++c) {
             const int incl = wave_scan_incl(tot[c]);
@@ -122,52 +143,89 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                 }
             }
         }
-        // ---- pieces: C slots each.  C = the mean number of row tiles per loaded expert, or, when that
-        //      exceeds SCHED_PIECE_MAX, that mean cut into the fewest equal parts that fit ------------
-        const int En = tot[5] > 0 ? tot[5] : 1;
-        const int parts = (MT + En * SCHED_PIECE_MAX - 1) / (En * SCHED_PIECE_MAX);  // ceil(mean / max)
-        int C = parts <= 1 ? (MT + En / 2) / En : (MT + En * parts - 1) / (En * parts);
-        C = C < 1 ? 1 : (C > SCHED_PIECE_MAX ? SCHED_PIECE_MAX : C);
+        // ---- pieces and the dense queue of every XCD -------------------------------------------
         const int mte_mine = (nblk_e + cap - 1) / cap;
-        const int pp_incl = block_scan_incl((mte_mine + C - 1) / C, s_part);
-        __syncthreads();  // s_mte / s_pre of the previous table are no longer read
-        s_mte[tid] = mte_mine;
-        s_pre[tid + 1] = pp_incl;
-        if (tid == 0) s_pre[0] = 0;
-        __syncthreads();
-        const int n_pieces = s_pre[E_local] * nt;
+        // second attempt: single-tile pieces, whose queues (at most ceil(MT * nt / 8) long) always fit
+        for (int attempt = 0; attempt < 2; ++attempt) {
+            int cmax = 1;
+            if (attempt == 0) {
+                const long long per64 = (long long)MT * nt / 64;
+                cmax = per64 < 1 ? 1 : (per64 > SCHED_PIECE_MAX ? SCHED_PIECE_MAX : (int)per64);
+            }
+            int pp = (mte_mine + cmax - 1) / cmax;
+            if (pp > 1 && (pp & 1) == 0) ++pp;
+            if (pp > mte_mine) pp = mte_mine;
+            const int pp_incl = block_scan_incl(pp, s_part);
+            int mine[8];
+            {
+                const int P0 = (pp_incl - pp) * nt, n = pp * nt;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                    const int q0 = (x - P0) & 7;
+                    const int cnt = q0 < n ? (n - q0 + 7) / 8 : 0;
+                    mine[x] = cnt > 0 ? sched_tiles_before(cnt, q0, mte_mine, pp) : 0;
+                }
+            }
+            __syncthreads();  // the tables of the previous attempt or GEMM are no longer read
+            s_mte[tid] = mte_mine;
+            s_pre[tid + 1] = pp_incl;
+            if (tid == 0) s_pre[0] = 0;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                mine[x] = wave_scan_incl(mine[x]);
+                if (lane == 63) s_wave[x][wave] = mine[x];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                int v = mine[x];
+                for (int ww = 0; ww < wave; ++ww) v += s_wave[x][ww];
+                s_len[x][tid + 1] = v;
+                if (tid == 0) s_len[x][0] = 0;
+            }
+            __syncthreads();
+            int longest = 0;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) longest = max(longest, s_len[x][E_local]);
+            if (8 * longest <= grid) break;  // uniform
+        }
 
         for (int b = blockIdx.x * 256 + tid; b < grid; b += gridDim.x * 256) {
-            const int x = b & 7, slot = b >> 3;
-            const int piece = (slot / C) * 8 + x, pos = slot % C;
+            const int x = b & 7, j = b >> 3;
             TileDesc td;
             td.expert = 0; td.row0 = 0; td.rows = 0; td.n0 = 0;
-            if (piece < n_pieces) {
-                // the expert e with s_pre[e] * nt <= piece < s_pre[e + 1] * nt
+            if (j < s_len[x][E_local]) {
+                // the expert e with s_len[x][e] <= j < s_len[x][e + 1]
                 int lo = 0, hi = E_local;
                 while (hi - lo > 1) {
                     int mid = (lo + hi) >> 1;
-                    if (s_pre[mid] * nt <= piece) lo = mid; else hi = mid;
+                    if (s_len[x][mid] <= j) lo = mid; else hi = mid;
                 }
                 const int e = lo;
                 const int mte = s_mte[e], pp = s_pre[e + 1] - s_pre[e];
-                const int q = piece - s_pre[e] * nt;
-                // the expert's row tiles are dealt evenly to its pp pieces per weight-row tile
-                const int ni = q / pp, pc = q % pp;
+                const int q0 = (x - s_pre[e] * nt) & 7;
                 const int pbase = mte / pp, prem = mte % pp;
-                const int mi = pc * pbase + min(pc, prem) + pos;
-                if (pos < pbase + (pc < prem ? 1 : 0)) {
-                    const int e_rows = s_off[e + 1] - s_off[e];
-                    // 32-row blocks of the expert, dealt evenly to its mte tiles
-                    const int nblk = (e_rows + 31) / 32;
-                    const int base = nblk / mte, rem = nblk % mte;
-                    const int blk0 = mi * base + min(mi, rem);
-                    const int nb = base + (mi < rem ? 1 : 0);
-                    td.expert = e;
-                    td.row0 = s_off[e] + blk0 * 32;
-                    td.rows = min(nb * 32, e_rows - blk0 * 32);
-                    td.n0 = ni * bn;
+                // pp consecutive pieces of this queue hold mte tiles; walk the last, partial run
+                const int r = j - s_len[x][e];
+                int pos = r % mte;
+                int q = q0 + 8 * ((r / mte) * pp);
+                for (;; q += 8) {
+                    const int len = pbase + ((q % pp) < prem ? 1 : 0);
+                    if (pos < len) break;
+                    pos -= len;
                 }
+                const int ni = q / pp, pc = q % pp;
+                const int mi = pc * pbase + min(pc, prem) + pos;
+                const int e_rows = s_off[e + 1] - s_off[e];
+                // 32-row blocks of the expert, dealt evenly to its mte tiles
+                const int nblk = (e_rows + 31) / 32;
+                const int base = nblk / mte, rem = nblk % mte;
+                const int blk0 = mi * base + min(mi, rem);
+                const int nb = base + (mi < rem ? 1 : 0);
+                td.expert = e;
+                td.row0 = s_off[e] + blk0 * 32;
+                td.rows = min(nb * 32, e_rows - blk0 * 32);
+                td.n0 = ni * bn;
             }
             table[b] = td;
         }
@@ -176,9 +234,10 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
 
 // ------------------------------------------------------------------------------------------------
 // Host side: tile classes, plans, launches.  Class ids index the variants listed in
-// moe_gemm_kernel.h: 0 = 128-row tiles (very low loads), 1 = 256-row tiles (main), 2 = 64, 3 = 32.
+// moe_gemm_kernel.h: 0 = 128-row tiles (very low loads), 1 = 288-row tiles (main), 2 = 64, 3 = 32,
+// 4 = 256.
 // ------------------------------------------------------------------------------------------------
-static const int kClassRows[GEMM_NUM_CLASSES] = {128, 256, 64, 32};
+static const int kClassRows[GEMM_NUM_CLASSES] = {128, 288, 64, 32, 256};
 constexpr int GEMM_BN = 256;
 
 #define DECL(name)                                                                                         \
@@ -192,7 +251,7 @@ DECL(swiglu) DECL(plain) DECL(pairsum)
 int gemm_class_rows(int cls) { return kClassRows[cls]; }
 
 int gemm_pick_class(double rows_per_expert) {
-    // Measured on the expert-parallel share (32 experts, Zipf loads): the 256-row class wins from
+    // Measured on the expert-parallel share (32 experts, Zipf loads): the tall class wins from
     // about 32 rows per expert upwards; at 8 rows per expert the 128-row class streams the weights
     // about 1 % faster.
     return rows_per_expert < 12.0 ? GEMM_LOW : GEMM_MAIN;
@@ -251,8 +310,8 @@ hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2
 struct RouterPick { int cls, nsplit; };
 static RouterPick router_gemm_pick(int T, int d, int Rp, int max_split) {
     const int nt = (Rp + GEMM_BN - 1) / GEMM_BN, KT = d / 64;
-    static const int order[GEMM_NUM_CLASSES] = {1, 0, 2, 3};  // tallest tile first
-    for (int i = 0; i < GEMM_NUM_CLASSES; ++i) {
+    static const int order[4] = {4, 0, 2, 3};  // tallest tile first (256, 128, 64, 32 rows)
+    for (int i = 0; i < 4; ++i) {
         const int c = order[i];
         const int mt = (T + kClassRows[c] - 1) / kClassRows[c];
         for (int s = 1; s <= 8 && s <= max_split; ++s)

@@ -30,8 +30,13 @@
 //     fragments of the next stage are read under those MFMAs, and the loads of a K step are spread
 //     one by one over its MFMA slots (bursts from four lockstep wavefronts overrun the compute
 //     unit's single vector-memory pipe and stall MFMA issue).
+//   * the tallest tile has 288 rows: 9 row blocks x 2 weight blocks accumulator blocks of 16 registers: the 256
+//     AGPRs hold eight row blocks, the ninth accumulates in VGPRs.  The compiler will not split one
+//     array of accumulators over the two files without shuffling them inside the K loop, so the
+//     MFMAs of the ninth block are inline asm with a VGPR constraint; they come first in every
+//     sub-step because the compiler cannot see that they are MFMAs (see mfma_pinned_vgpr).
 //   * work items are ordered so that the workgroups running concurrently on one XCD share weight
-//     panels through that XCD's L2.
+//     panels through that XCD's L2, and so that each XCD's queue of work items is dense.
 #pragma once
 #include <stdlib.h>
 
@@ -156,6 +161,17 @@ static __device__ inline void static_for(F&& f) {
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
+// Row tiles of more than 256 rows need more than the 256 accumulator registers (AGPRs) of a lane: the
+// blocks past the eighth accumulate in ordinary VGPRs.  The compiler's own allocation shuffles such
+// accumulators between the two files inside the K loop, so the MFMAs of those blocks are issued through
+// inline asm with a VGPR operand constraint (the others stay builtins and then all fit the AGPRs).
+// The asm is opaque to the compiler's hazard recogniser, which would otherwise keep a reader of an MFMA
+// result the required wait states behind it: the caller places these MFMAs where at least three other
+// 32x32x16 MFMAs follow before anything else can read the result.
+static __device__ inline void mfma_pinned_vgpr(f32x16_t& acc, const bf16x8_t& w, const bf16x8_t& x) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(w), "v"(x));
+}
+
 // s_waitcnt vmcnt(n) for a wave-uniform run-time n (the instruction takes an immediate)
 static __device__ inline void wait_vmcnt_rt(int n) {
     switch (n) {
@@ -188,7 +204,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
     constexpr int STAGE = BM * CH;            // 16-byte chunks per token stage
     constexpr int BLK = 32 * CH * 16;         // bytes between consecutive 32-row blocks in a stage
     static_assert(FN == 2 && KK == 4, "wave tile");
-    static_assert(BM % 32 == 0 && FM >= 1 && FM <= 8, "row tile");
+    static_assert(BM % 32 == 0 && FM >= 1 && FM <= 9, "row tile");
     static_assert(NSX >= 3 && (2 * FM + WL) <= 32, "pipeline depth");
 
     extern __shared__ u32x4_t lds[];  // [NSX][STAGE]
@@ -331,8 +347,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<NM>([&](auto m_c) {
                     constexpr int m = decltype(m_c)::value;
-                    constexpr int b = m / FN, a = m % FN;
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[BUF][kk][a], xf[cur][b], acc[a][b], 0, 0, 0);
+                    // a ninth row block goes first: whatever reads its result next (the compiler may
+                    // copy it at the end of a basic block) then sits behind the sub-step's other MFMAs
+                    constexpr int a = m % FN;
+                    constexpr int b = FMV <= 8 ? m / FN : (m / FN + 8) % 9;
+                    if constexpr (b < 8) {
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[BUF][kk][a], xf[cur][b], acc[a][b], 0, 0, 0);
+                    } else {
+                        mfma_pinned_vgpr(acc[a][b], wr[BUF][kk][a], xf[cur][b]);
+                    }
                     // first half of the slots: LDS reads of the next sub-step's token fragments, early
                     // enough that their latency is covered by the MFMAs of the second half
                     if constexpr (m < FMV) {
@@ -389,7 +412,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
     case n:                                                            \
         if constexpr (n <= FM) main_loop(std::integral_constant<int, (n <= FM ? n : 1)>{}); \
         break;
-        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8)
+        CASE(1) CASE(2) CASE(3) CASE(4) CASE(5) CASE(6) CASE(7) CASE(8) CASE(9)
 #undef CASE
         default: break;
     }
@@ -401,14 +424,15 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
 
 // ---- per-epilogue instantiation units ----------------------------------------------------------
 // Classes 0 and 1 are the production token-tile classes (row tiles of up to 128 rows for very low
-// loads, up to 256 rows otherwise); higher ids are alternatives kept for tuning runs
+// loads, up to 288 rows otherwise); higher ids are alternatives kept for tuning runs
 // (moe_set_tile_class).
 //   V(id, BM, NSX)
 #define FOR_EACH_VARIANT(V) \
     V(0, 128, 4)            \
-    V(1, 256, 4)            \
+    V(1, 288, 4)            \
     V(2, 64, 4)             \
-    V(3, 32, 4)
+    V(3, 32, 4)             \
+    V(4, 256, 4)
 
 template <int BM, int NSX, int EPI>
 struct Variant {

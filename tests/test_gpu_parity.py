@@ -179,8 +179,17 @@ FFN_CASES = [
     ("main_big", 4, 256, 320, 1500, 1),
     ("low_wide", 3, 320, 448, 70, 0),        # d, f not multiples of the 256-row weight tile
     ("main_narrow", 2, 64, 64, 700, 1),
-    ("swp256", 4, 256, 320, 1500, 2),
-    ("swp320", 4, 192, 320, 1300, 3),
+    ("rows64_class", 4, 256, 320, 1500, 2),
+    ("rows32_class", 4, 192, 320, 1300, 3),
+    ("rows256_class", 3, 256, 320, 2000, 4),
+    ("rows256_ragged", 5, 192, 128, 1463, 4),
+    ("many_tiles_per_expert", 2, 128, 192, 5000, 1),   # > 8 row tiles per expert: several pieces per weight tile
+    # work-list layouts: pieces of unequal length (odd piece counts), many experts with few tiles each
+    # over several weight-row tiles, single-tile pieces
+    ("sched_uneven_pieces", 3, 64, 1024, 12000, 1),
+    ("sched_uneven_pieces_256", 3, 64, 1024, 12000, 4),
+    ("sched_many_experts", 40, 64, 640, 9000, 1),
+    ("sched_single_tile_pieces", 3, 64, 384, 12000, 1),
     ("auto", 8, 128, 256, 640, -1),
 ]
 
@@ -219,7 +228,7 @@ def test_grouped_ffn_all_rows_in_one_expert_and_rows_cap_larger_than_used(moe):
     xp = wl.gaussian_bf16_bits(8, 9, (cap, d), 1.0)
     ctx = moe.MoEContext(cap, d, f, E_local, 1)
     packed = ctx.moe_pack_weights(gu.to_dev_bf16(W1), gu.to_dev_bf16(W3), gu.to_dev_bf16(W2))
-    for cls in range(4):
+    for cls in range(5):
         ctx.moe_set_tile_class(cls)
         y = torch.full((cap, d), 7.0, dtype=torch.bfloat16, device="cuda")
         ctx.moe_grouped_ffn(gu.to_dev_bf16(xp), gu.to_dev(off), cap, packed, y=y)
@@ -295,7 +304,7 @@ def test_layer_parity(moe, case):
     ctx.close()
 
 
-@pytest.mark.parametrize("cls", list(range(4)))
+@pytest.mark.parametrize("cls", list(range(5)))
 def test_layer_parity_every_tile_class(moe, cls):
     print(f"layer tile class {cls}", flush=True)
     inp = wl.custom("cls", 700, 128, 256, 8, 2, seed=cls, wg_std=0.08, w_std=0.06)
