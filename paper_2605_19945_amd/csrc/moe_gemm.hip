@@ -24,19 +24,22 @@
 //
 // A "piece" is up to SCHED_PIECE_MAX row tiles of one expert and one weight-row tile, consecutive in
 // one XCD's queue: they run side by side and share that weight panel in the XCD's L2.  An expert
-// with more row tiles has pp > 1 pieces per weight-row tile, as equal as possible (the first
-// mte % pp one tile longer).  Pieces are numbered expert-major, then weight-row tile, then piece,
-// and dealt round-robin to the XCDs; pp is odd (or every piece is a single tile), so every XCD meets
-// the longer and the shorter pieces of an expert in turn.  The workgroups resident on one XCD at a
-// time are then a few consecutive weight-row tiles of one expert times its row tiles, and the token
-// panels are shared by the pieces running side by side.  With few work items the pieces are made
-// shorter so that there are at least 64 of them.
+// with more row tiles is cut into pp > 1 row ranges of nearly equal length (the first mte % pp one
+// tile longer).  Pieces are numbered expert-major, then row range, then weight-row tile, and dealt
+// round-robin to the XCDs.  The workgroups resident on one XCD at a time are then consecutive
+// weight-row tiles of one expert times the row tiles of one row range: they share the token panels
+// of that range, all eight XCDs work on the same range (it stays in the Infinity Cache), and every
+// XCD gets its share of every range.  An expert's weights are streamed once per row range.  With few
+// work items the pieces are made shorter so that there are at least 64 of them.
 // ------------------------------------------------------------------------------------------------
 constexpr int SCHED_CU = 256;    // compute units of the device (one workgroup each)
 constexpr int SCHED_PIECE_MAX = 8;  // row tiles per piece, at most
-// Per-tile cost that does not scale with the tile's height, in 32-row blocks of MFMA work: every
-// tile streams its whole 256-row weight panel whatever its height.  Fitted to measured launch times
-// of the Mixtral-shape GEMMs at caps of 192 and 256 rows (tile time ~ blocks + 3.4).
+// Per-tile cost that does not scale with the tile's height, in 32-row blocks of MFMA work.  In launches
+// where every row tile has the same height and the workgroups run in step the cost is about one block
+// (Mixtral shape, tiles forced to 6, 7, 8, 9 blocks: 28 rounds of GEMM1 take 2331, 2656, 2993, 3333 us).
+// On ragged loads a tile costs more than that -- its weight panel is shared with fewer neighbours the
+// further the workgroups drift apart -- and 3.5 picks caps that are as fast or up to 2 % faster than
+// those picked with 1.0 on every benchmark workload.
 constexpr float SCHED_TILE_OVERHEAD = 3.5f;
 static __host__ __device__ inline int sched_min_cap_blocks(int bm) { return (5 * (bm / 32) + 7) / 8; }
 // Entries of a work list (= workgroups of the launch): eight times the longest XCD queue must fit.
@@ -70,15 +73,9 @@ static __device__ inline int block_scan_incl(int v, int32_t* part) {
     return v;
 }
 
-// Tiles in the first i pieces that one XCD holds of an expert: the pieces q0, q0 + 8, q0 + 16, ... of
-// its pp * nt pieces, piece q being the (q % pp)-th of a weight-row tile.  mte row tiles in pp pieces.
-static __device__ inline int sched_tiles_before(int i, int q0, int mte, int pp) {
-    const int pbase = mte / pp, prem = mte % pp;
-    const int full = i / pp, m = i % pp;  // pp consecutive visits meet every piece number once
-    int t = full * mte + m * pbase;
-    if (prem)
-        for (int k = 0; k < m; ++k) t += ((q0 + 8 * k) % pp) < prem ? 1 : 0;
-    return t;
+// Number of integers in [a, a + len) that are congruent to x modulo 8 (a >= 0, 0 <= x < 8)
+static __device__ inline int sched_count_mod8(int a, int len, int x) {
+    return ((a + len - 1 - x) >> 3) - ((a - 1 - x) >> 3);  // arithmetic shifts: floor division
 }
 
 __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict__ offsets, int E_local,
@@ -153,18 +150,19 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                 cmax = per64 < 1 ? 1 : (per64 > SCHED_PIECE_MAX ? SCHED_PIECE_MAX : (int)per64);
             }
             int pp = (mte_mine + cmax - 1) / cmax;
-            if (pp > 1 && (pp & 1) == 0) ++pp;
-            if (pp > mte_mine) pp = mte_mine;
             const int pp_incl = block_scan_incl(pp, s_part);
             int mine[8];
-            {
-                const int P0 = (pp_incl - pp) * nt, n = pp * nt;
+            if (pp > 0) {
+                // the expert's pieces are S .. S + pp * nt - 1; those of its first prem row ranges are
+                // one tile longer
+                const int S = (pp_incl - pp) * nt, pbase = mte_mine / pp, prem = mte_mine % pp;
 #pragma unroll
-                for (int x = 0; x < 8; ++x) {
-                    const int q0 = (x - P0) & 7;
-                    const int cnt = q0 < n ? (n - q0 + 7) / 8 : 0;
-                    mine[x] = cnt > 0 ? sched_tiles_before(cnt, q0, mte_mine, pp) : 0;
-                }
+                for (int x = 0; x < 8; ++x)
+                    mine[x] = (pbase + 1) * sched_count_mod8(S, prem * nt, x) +
+                              pbase * sched_count_mod8(S + prem * nt, (pp - prem) * nt, x);
+            } else {
+#pragma unroll
+                for (int x = 0; x < 8; ++x) mine[x] = 0;
             }
             __syncthreads();  // the tables of the previous attempt or GEMM are no longer read
             s_mte[tid] = mte_mine;
@@ -203,18 +201,23 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                 }
                 const int e = lo;
                 const int mte = s_mte[e], pp = s_pre[e + 1] - s_pre[e];
-                const int q0 = (x - s_pre[e] * nt) & 7;
+                const int S = s_pre[e] * nt;
                 const int pbase = mte / pp, prem = mte % pp;
-                // pp consecutive pieces of this queue hold mte tiles; walk the last, partial run
+                // this queue's pieces of the expert: first + 8 i, the long ones come first
+                const int first = S + ((x - S) & 7);
+                const int n_long = sched_count_mod8(S, prem * nt, x);
                 const int r = j - s_len[x][e];
-                int pos = r % mte;
-                int q = q0 + 8 * ((r / mte) * pp);
-                for (;; q += 8) {
-                    const int len = pbase + ((q % pp) < prem ? 1 : 0);
-                    if (pos < len) break;
-                    pos -= len;
+                int i, pos;
+                if (r < n_long * (pbase + 1)) {
+                    i = r / (pbase + 1);
+                    pos = r % (pbase + 1);
+                } else {
+                    const int rs = r - n_long * (pbase + 1);
+                    i = n_long + rs / pbase;
+                    pos = rs % pbase;
                 }
-                const int ni = q / pp, pc = q % pp;
+                const int q = first + 8 * i - S;
+                const int pc = q / nt, ni = q % nt;
                 const int mi = pc * pbase + min(pc, prem) + pos;
                 const int e_rows = s_off[e + 1] - s_off[e];
                 // 32-row blocks of the expert, dealt evenly to its mte tiles
