@@ -119,6 +119,68 @@ static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileD
     }
 }
 
+// bf16 epilogues (EPI_PLAIN, EPI_SWIGLU) through LDS.  Stored straight from the accumulators, a wave-level
+// store would write 16 bytes to each of 32 rows; instead every wavefront parks its 64 output columns (32 after SwiGLU) of all rows in its own quarter of
+// the token ring, which nobody reads any more, and writes them back out row-contiguously: 16 bytes per
+// lane, whole 128-byte (64-byte) runs per row.  Rows are ROWB bytes apart in LDS with the 16-byte chunks
+// XOR-swizzled by row so that both the 8-byte writes (32 rows at one column) and the 16-byte reads (8 or
+// 16 rows at all columns) are spread over the banks.  Worth 0.2 % (Mixtral shape, 64 to 224 K steps per
+// tile) to 1.8 % (f = 768: 12 K steps per tile) of the layer time; most of the cost of the scattered
+// stores was their completion, which the wavefronts never waited for.
+// The caller has made sure that no wavefront still reads the ring.
+template <int FM, int FN, int BM, int TN, int EPI>
+static __device__ inline void gemm_epilogue_staged(f32x16_t (&acc)[FN][FM], const TileDesc& td, int Np,
+                                                   uint16_t* __restrict__ C, int ldc, int wn, int lane,
+                                                   char* lds_base) {
+    static_assert(EPI == EPI_PLAIN || EPI == EPI_SWIGLU, "bf16 outputs");
+    static_assert(FN == 2 && TN == 64, "wave tile");
+    constexpr int OUTC = EPI == EPI_SWIGLU ? TN / 2 : TN;  // output columns of this wavefront per row
+    constexpr int ROWB = OUTC * 2;                         // 128 or 64 bytes per row
+    constexpr int NCH = ROWB / 16;                         // 16-byte chunks per row: 8 or 4
+    char* stage = lds_base + wn * (BM * ROWB);
+    const int frow = lane & 31, fhalf = lane >> 5;
+    auto swz = [](int r) { return EPI == EPI_SWIGLU ? (r >> 2) & 3 : (r ^ (r >> 3)) & 7; };
+#pragma unroll
+    for (int b = 0; b < FM; ++b) {
+        if (b * 32 >= td.rows) break;  // uniform
+        const int r = b * 32 + frow;
+        char* srow = stage + r * ROWB + 8 * fhalf;
+        const int x = swz(r);
+        if constexpr (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float h[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) h[v] = silu_f32(acc[0][b][4 * q + v]) * acc[1][b][4 * q + v];
+                u32x2_t o;
+                o.x = pack2_bf16(h[0], h[1]);
+                o.y = pack2_bf16(h[2], h[3]);
+                *(u32x2_t*)(srow + ((q ^ x) << 4)) = o;
+            }
+        } else {
+#pragma unroll
+            for (int a = 0; a < FN; ++a)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    u32x2_t o;
+                    o.x = pack2_bf16(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]);
+                    o.y = pack2_bf16(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                    *(u32x2_t*)(srow + (((4 * a + q) ^ x) << 4)) = o;
+                }
+        }
+    }
+    // the wavefront reads back only what it wrote itself
+    const int prow = td.n0 + wn * TN;  // first packed weight row of this wavefront
+    if (prow >= Np) return;            // Np is a multiple of 64
+    constexpr int RPI = 64 / NCH;      // rows per wave-level store
+    const int ch = lane % NCH;
+    uint16_t* cbase = C + (size_t)td.row0 * ldc + (EPI == EPI_SWIGLU ? prow / 2 : prow) + ch * 8;
+    for (int r = lane / NCH; r < td.rows; r += RPI) {
+        const u32x4_t v = *(const u32x4_t*)(stage + r * ROWB + ((ch ^ swz(r)) << 4));
+        *(u32x4_t*)(cbase + (size_t)r * ldc) = v;
+    }
+}
+
 template <int CH>
 static __device__ inline int swz_of(int r) {
     // LDS: 64 banks x 4 B; a ds_read_b128 is served 16 lanes (256 B) per cycle.  The 16 rows a
@@ -417,7 +479,14 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
         default: break;
     }
 
-    gemm_epilogue<FM, FN, BM, TN, EPI>(acc, td, Np, C, ldc, 0, wave, lane);
+    if constexpr (EPI == EPI_PLAIN || EPI == EPI_SWIGLU) {
+        static_assert(NSX >= 4, "the staged epilogue uses four quarters of BM x 128 bytes");
+        // every wavefront has issued and completed its last reads of the token ring
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        gemm_epilogue_staged<FM, FN, BM, TN, EPI>(acc, td, Np, C, ldc, wave, lane, (char*)lds);
+    } else {
+        gemm_epilogue<FM, FN, BM, TN, EPI>(acc, td, Np, C, ldc, 0, wave, lane);
+    }
 }
 
 
