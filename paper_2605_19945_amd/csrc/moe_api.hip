@@ -30,7 +30,7 @@ bool shape_ok(const moe_shape* s) {
 }
 
 struct Layout {
-    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, table_r, logits, route_ws, H, Y, total;
+    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, table_r, logits, route_ws, H, Y, part, total;
     int table1_cap, table2_cap;
     int64_t rows_cap;
 };
@@ -71,6 +71,7 @@ Layout make_layout(const moe_shape* s) {
     L.route_ws = take((size_t)MOE_ROUTE_WS_INTS * 4);
     L.H = take((size_t)L.rows_cap * moe_ld_pad(s->f) * 2);
     L.Y = take((size_t)L.rows_cap * s->d * 2);
+    L.part = take(moe_part_bytes(L.rows_cap, s->d));
     L.total = o;
     return L;
 }
@@ -171,6 +172,8 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     c->logits = (float*)(c->ws + L.logits);
     c->H = (uint16_t*)(c->ws + L.H);
     c->Y = (uint16_t*)(c->ws + L.Y);
+    c->part = (float*)(c->ws + L.part);
+    c->part_bytes = moe_part_bytes(L.rows_cap, s->d);
     c->rows_cap = L.rows_cap;
     c->table1_cap = L.table1_cap;
     c->table2_cap = L.table2_cap;
@@ -288,7 +291,9 @@ static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t*
     e = launch_gemm1(p, X, s.d, row_map, w13f, s.d, s.f, c->H, c->table1, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM2], st);
-    e = launch_gemm2(p, c->H, w2f, s.d, s.f, Y, c->table2, st);
+    // offsets[E_local] = the rows actually present
+    const int nsplit = gemm_pick_split2(p, n_rows_cap, s.E_local, s.d, s.f, c->part_bytes);
+    e = launch_gemm2(p, c->H, w2f, s.d, s.f, Y, c->table2, nsplit, c->part, n_rows_cap, offsets + s.E_local, st);
     return from_hip(e);
 }
 

@@ -1,5 +1,5 @@
 // Work list, tile classes, plans and launches of the grouped GEMMs (the kernel itself lives in
-// moe_gemm_kernel.h and is instantiated per epilogue in moe_gemm_{swiglu,plain,pairsum}.hip).
+// moe_gemm_kernel.h and is instantiated per epilogue in moe_gemm_{swiglu,plain,pairsum,partial}.hip).
 #include "moe_internal.h"
 
 // ------------------------------------------------------------------------------------------------
@@ -248,7 +248,7 @@ constexpr int GEMM_BN = 256;
     hipError_t gemm_launch_##name(int cls, int grid, const uint16_t* X, int ldx, const int32_t* row_map,   \
                                   const uint16_t* Wf, int Np, int K, uint16_t* C, int ldc,                 \
                                   const TileDesc* table, int nsplit, size_t c_split_bytes, hipStream_t st);
-DECL(swiglu) DECL(plain) DECL(pairsum)
+DECL(swiglu) DECL(plain) DECL(pairsum) DECL(partial)
 #undef DECL
 
 int gemm_class_rows(int cls) { return kClassRows[cls]; }
@@ -279,6 +279,7 @@ hipError_t gemm_init_attributes() {
     hipError_t err = gemm_set_attr_swiglu();
     if (err == hipSuccess) err = gemm_set_attr_plain();
     if (err == hipSuccess) err = gemm_set_attr_pairsum();
+    if (err == hipSuccess) err = gemm_set_attr_partial();
     return err;
 }
 
@@ -299,10 +300,77 @@ hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int
     return gemm_launch_swiglu(p.cls, p.grid1, X, ldx, row_map, W13f, 2 * f, d, H, moe_ld_pad(f), table, 1, 0, st);
 }
 
+// Reduction splits of the second expert GEMM.  With few resident experts and few rows it has far fewer
+// work items than the device has compute units (Mixtral shape: 16 weight-row tiles x 8 experts = 128), and
+// each item streams a 256 x f weight panel at what ONE compute unit can pull.  Cutting the reduction into
+// nsplit ranges multiplies the items; the partial sums go to fp32 slabs and are added in slab order.
+// Estimated time of a launch in units of one unsplit item: rounds * (1 / nsplit + fixed cost per item),
+// plus the slab traffic relative to the weights.  The row tiles are estimated from the mean load (the
+// host does not know the per-expert counts).  Only for launches that are bound by weight streaming: from
+// about 256 rows per expert on, the idle compute units are not a loss, the busy ones run at a higher
+// clock within the same power (Mixtral shape: splits give -7 % layer time at 128 rows per expert, +3 %
+// at 256).
+int gemm_pick_split2(const GemmPlan& p, int64_t n_rows, int E_local, int d, int f, size_t part_bytes) {
+    if (n_rows <= 0) return 1;
+    const int64_t e_loaded = n_rows < E_local ? n_rows : E_local;
+    if (n_rows > 160 * e_loaded) return 1;
+    const int64_t tiles = e_loaded * ((n_rows / e_loaded + p.bm - 1) / p.bm);
+    const double items = (double)tiles * p.nt2;
+    const double w_bytes = (double)e_loaded * d * f * 2;
+    const int KT = f / 64;
+    auto cost = [&](int s) {
+        const double rounds = (double)(((int64_t)(items * s) + SCHED_CU - 1) / SCHED_CU);
+        double c = rounds * (1.0 / s + 0.06);
+        if (s > 1) c += 0.02 + 2.0 * s * (double)n_rows * d * 4 / w_bytes * (items / SCHED_CU);
+        return c;
+    };
+    int best = 1;
+    double best_cost = cost(1) * 0.9;  // a split has to win by 10 %
+    for (int s = 2; s <= 8; ++s) {
+        if (KT % s != 0 || KT / s < 16) continue;
+        if ((double)s * n_rows * d * 4 > (double)part_bytes) continue;
+        const double c = cost(s);
+        if (c < best_cost) {
+            best_cost = c;
+            best = s;
+        }
+    }
+    return best;
+}
+
+// Y[r, c] = bf16(sum over the slabs of part[s][r][c]) for the rows r < *n_rows_dev
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, int nsplit,
+                                                            size_t slab_elems, const int32_t* __restrict__ n_rows_dev,
+                                                            int d, uint16_t* __restrict__ Y) {
+    const size_t n = (size_t)*n_rows_dev * d / 4;  // quads of columns
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        f32x4_t acc = *(const f32x4_t*)(part + 4 * i);
+        for (int s = 1; s < nsplit; ++s) {
+            const f32x4_t v = *(const f32x4_t*)(part + s * slab_elems + 4 * i);
+            acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+        }
+        u32x2_t o;
+        o.x = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)acc[0]) | ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)acc[1]) << 16);
+        o.y = (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)acc[2]) | ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)acc[3]) << 16);
+        *(u32x2_t*)(Y + 4 * i) = o;
+    }
+}
+
 hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2f, int d, int f, uint16_t* Y,
-                        const TileDesc* table, hipStream_t st) {
+                        const TileDesc* table, int nsplit, float* part, int64_t n_rows, const int32_t* n_rows_dev,
+                        hipStream_t st) {
     if (p.grid2 <= 0) return hipSuccess;
-    return gemm_launch_plain(p.cls, p.grid2, H, moe_ld_pad(f), nullptr, W2f, d, f, Y, d, table, 1, 0, st);
+    if (nsplit <= 1)
+        return gemm_launch_plain(p.cls, p.grid2, H, moe_ld_pad(f), nullptr, W2f, d, f, Y, d, table, 1, 0, st);
+    const size_t slab_elems = (size_t)n_rows * d;
+    hipError_t e = gemm_launch_partial(p.cls, p.grid2, H, moe_ld_pad(f), nullptr, W2f, d, f / nsplit, (uint16_t*)part, d,
+                                       table, nsplit, slab_elems * 4, st);
+    if (e != hipSuccess) return e;
+    size_t blocks = (slab_elems / 4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)part, nsplit,
+                       slab_elems, n_rows_dev, d, Y);
+    return hipGetLastError();
 }
 
 // ---- router logits as a one-group GEMM (E >= 32): logits[T, Ep] = x[T, d] * Wg, fp32 ------------

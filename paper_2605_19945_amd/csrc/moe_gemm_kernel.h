@@ -53,7 +53,7 @@ static __device__ inline uint32_t pack2_bf16(float a, float b) {
 }
 static __device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
 
-enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_PAIR_SUM_F32 = 2 };
+enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_PAIR_SUM_F32 = 2, EPI_PARTIAL_F32 = 3 };
 
 // Epilogues.  Accumulator element v of lane l in block (a, b) is
 //   weight row  a*32 + 8*(v/4) + 4*(l/32) + v%4,   token row  b*32 + l%32,
@@ -82,6 +82,21 @@ static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileD
 #pragma unroll
                     for (int v = 0; v < 4; ++v) o[v] = acc[2 * a2][b][4 * q + v] + acc[2 * a2 + 1][b][4 * q + v];
                     *(f32x4_t*)(frow_out + col + 8 * q) = o;
+                }
+            }
+        } else if constexpr (EPI == EPI_PARTIAL_F32) {
+            // partial sums of a reduction split, fp32 (C is a float matrix, one slab per split)
+            float* frow_out = (float*)C + (size_t)(td.row0 + trow) * ldc;
+#pragma unroll
+            for (int a = 0; a < FN; ++a) {
+                const int col = td.n0 + wn * TN + a * 32;
+                if (col >= Np) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4_t o;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) o[v] = acc[a][b][4 * q + v];
+                    *(f32x4_t*)(frow_out + col + 4 * fhalf + 8 * q) = o;
                 }
             }
         } else if constexpr (EPI == EPI_SWIGLU) {
@@ -542,6 +557,8 @@ struct Variant {
 #define MOE_GEMM_SET_ATTR_EPI_PLAIN(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PLAIN, bm, ns)
 #define MOE_GEMM_SET_ATTR_EPI_SWIGLU(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_SWIGLU, bm, ns)
 #define MOE_GEMM_SET_ATTR_EPI_PAIR_SUM_F32(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PAIR_SUM_F32, bm, ns)
+#define MOE_GEMM_SET_ATTR_EPI_PARTIAL_F32(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PARTIAL_F32, bm, ns)
 #define MOE_GEMM_CASE_EPI_PLAIN(id, bm, ns) MOE_GEMM_CASE(EPI_PLAIN, id, bm, ns)
 #define MOE_GEMM_CASE_EPI_SWIGLU(id, bm, ns) MOE_GEMM_CASE(EPI_SWIGLU, id, bm, ns)
 #define MOE_GEMM_CASE_EPI_PAIR_SUM_F32(id, bm, ns) MOE_GEMM_CASE(EPI_PAIR_SUM_F32, id, bm, ns)
+#define MOE_GEMM_CASE_EPI_PARTIAL_F32(id, bm, ns) MOE_GEMM_CASE(EPI_PARTIAL_F32, id, bm, ns)

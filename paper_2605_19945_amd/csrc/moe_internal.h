@@ -52,6 +52,8 @@ struct moe_ctx {
     int32_t* route_ws;   // [MOE_ROUTE_WS_INTS] resident router: ticket (zero between launches) + partial counts
     uint16_t* H;         // [rows_cap, f] bf16
     uint16_t* Y;         // [rows_cap, d] bf16
+    float* part;         // fp32 partial sums of a reduction split of GEMM2: [nsplit][n_rows, d]
+    size_t part_bytes;
     int64_t rows_cap;
     int table1_cap, table2_cap;
     hipEvent_t (*ev)[MOE_NUM_STAGES + 1];  // ring of MOE_EVENT_RING event sets, or nullptr
@@ -61,6 +63,11 @@ struct moe_ctx {
 };
 
 static inline int64_t moe_round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+// Workspace for the partial sums of a split second GEMM: splits are only worth it at low loads
+static inline size_t moe_part_bytes(int64_t rows_cap, int d) {
+    const size_t want = (size_t)8 * rows_cap * d * 4, cap = (size_t)64 << 20;
+    return want < cap ? want : cap;
+}
 // Leading dimension (elements) of the intermediate H, which the library lays out itself: rows are
 // padded by 128 bytes so that the rows of a tile, which are all read at the same K offset, do not
 // fall on one L2 channel when K*2 is a power of two.
@@ -111,5 +118,7 @@ hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_loca
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table,
                         hipStream_t st);
-hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2f, int d, int f,
-                        uint16_t* Y, const TileDesc* table, hipStream_t st);
+int gemm_pick_split2(const GemmPlan& p, int64_t n_rows, int E_local, int d, int f, size_t part_bytes);
+hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2f, int d, int f, uint16_t* Y,
+                        const TileDesc* table, int nsplit, float* part, int64_t n_rows, const int32_t* n_rows_dev,
+                        hipStream_t st);

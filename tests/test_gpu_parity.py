@@ -190,6 +190,11 @@ FFN_CASES = [
     ("sched_uneven_pieces_256", 3, 64, 1024, 12000, 4),
     ("sched_many_experts", 40, 64, 640, 9000, 1),
     ("sched_single_tile_pieces", 3, 64, 384, 12000, 1),
+    # few work items and a long reduction: the second GEMM runs as 2 (f = 2048) or 4 (f = 4096) reduction
+    # splits with fp32 partial sums
+    ("gemm2_two_splits", 4, 128, 2048, 100, -1),
+    ("gemm2_four_splits", 8, 256, 4096, 300, 1),
+    ("gemm2_splits_low_class", 3, 320, 2048, 20, 0),
     ("auto", 8, 128, 256, 640, -1),
 ]
 
@@ -294,6 +299,7 @@ LAYER_CASES = [
     ("fine_small", lambda: wl.fine_grained(300, 0, d=256, f=128, E=128, k=8)),
     ("ep_small", lambda: wl.ep_share_layer(257, 0, d=256, f=192, E=64, k=6, e_lo=16, E_local=8)),
     ("k_eq_E", lambda: wl.custom("k_eq_E", 90, 128, 128, 4, 4, seed=9, wg_std=0.1, w_std=0.08)),
+    ("long_f_low_load", lambda: wl.custom("long_f_low_load", 40, 128, 2048, 4, 2, seed=11, wg_std=0.05, w_std=0.04)),
 ]
 
 
