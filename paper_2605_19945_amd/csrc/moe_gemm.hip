@@ -306,14 +306,15 @@ hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int
 // nsplit ranges multiplies the items; the partial sums go to fp32 slabs and are added in slab order.
 // Estimated time of a launch in units of one unsplit item: rounds * (1 / nsplit + fixed cost per item),
 // plus the slab traffic relative to the weights.  The row tiles are estimated from the mean load (the
-// host does not know the per-expert counts).  Only for launches that are bound by weight streaming: from
-// about 256 rows per expert on, the idle compute units are not a loss, the busy ones run at a higher
-// clock within the same power (Mixtral shape: splits give -7 % layer time at 128 rows per expert, +3 %
-// at 256).
+// host does not know the per-expert counts).  Only for launches that are bound by weight streaming: with
+// more rows per expert the idle compute units are not a loss, the busy ones run at a higher clock within
+// the same power (Mixtral shape, both expert GEMMs together, split against unsplit: 0.642 against 0.694
+// ms at 176 rows per expert, 0.656 against 0.705 at 192, 0.712 against 0.679 at 208, 0.757 against
+// 0.739 at 256).
 int gemm_pick_split2(const GemmPlan& p, int64_t n_rows, int E_local, int d, int f, size_t part_bytes) {
     if (n_rows <= 0) return 1;
     const int64_t e_loaded = n_rows < E_local ? n_rows : E_local;
-    if (n_rows > 160 * e_loaded) return 1;
+    if (n_rows > 192 * e_loaded) return 1;
     const int64_t tiles = e_loaded * ((n_rows / e_loaded + p.bm - 1) / p.bm);
     const double items = (double)tiles * p.nt2;
     const double w_bytes = (double)e_loaded * d * f * 2;
