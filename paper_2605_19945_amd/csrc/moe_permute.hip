@@ -4,7 +4,8 @@
 // experts" (Sec. 2.1); inside one GPU that is the grouping of rows by expert computed here.
 // Order inside an expert is ascending token id, so the result is unique and reproducible.
 //
-// Three small kernels, no atomics on global memory, no waiting between workgroups:
+// Three small kernels, no atomics on global memory, no waiting between workgroups (up to 512 tokens:
+// one kernel, one workgroup, the same steps):
 //   1. per-256-token block histogram of resident experts,
 //   2. one workgroup: exclusive scan over blocks (per expert) and over experts -> offsets,
 //   3. per block: rank of every assignment among the block's earlier tokens, from per-wavefront
@@ -98,9 +99,91 @@ __global__ __launch_bounds__(PB) void permute_rank_kernel(const int32_t* __restr
     }
 }
 
+// The same three steps in ONE workgroup, for up to PF_BLOCKS blocks of 256 tokens: at decode-sized
+// batches the three launches and the gaps between them cost more than the work (permute + work-list
+// stage at 64 tokens: 29 -> 17 us; from about four blocks on the three kernels are faster).
+constexpr int PF_BLOCKS = 2;
+__global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __restrict__ idx, int T, int k, int e_lo,
+                                                           int E_local, int32_t* __restrict__ offsets,
+                                                           int32_t* __restrict__ row_of,
+                                                           int32_t* __restrict__ tok_of) {
+    __shared__ int32_t hist[PF_BLOCKS * 256];         // [block][E_local] -> assignments to e in earlier blocks
+    __shared__ unsigned long long masks[PW * 256];   // [wave][E_local]
+    __shared__ int32_t wbase[PW * 256];
+    __shared__ int32_t tot[256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nblk = (T + PB - 1) / PB;
+    for (int o = tid; o < nblk * E_local; o += PB) hist[o] = 0;
+    __syncthreads();
+    for (int b = 0; b < nblk; ++b) {
+        const int t = b * PB + tid;
+        if (t < T)
+            for (int j = 0; j < k; ++j) {
+                const int e = idx[(size_t)t * k + j] - e_lo;
+                if (e >= 0 && e < E_local) atomicAdd(&hist[b * E_local + e], 1);
+            }
+    }
+    __syncthreads();
+    int run = 0;
+    if (tid < E_local)
+        for (int b = 0; b < nblk; ++b) {
+            const int c = hist[b * E_local + tid];
+            hist[b * E_local + tid] = run;
+            run += c;
+        }
+    tot[tid] = run;  // 0 beyond E_local
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {  // inclusive Hillis-Steele scan
+        const int v = tid >= off ? tot[tid - off] : 0;
+        __syncthreads();
+        tot[tid] += v;
+        __syncthreads();
+    }
+    if (tid < E_local) offsets[tid + 1] = tot[tid];
+    if (tid == 0) offsets[0] = 0;
+    for (int b = 0; b < nblk; ++b) {
+        for (int o = tid; o < PW * E_local; o += PB) masks[o] = 0ull;
+        __syncthreads();
+        const int t = b * PB + tid;
+        if (t < T)
+            for (int j = 0; j < k; ++j) {
+                const int e = idx[(size_t)t * k + j] - e_lo;
+                if (e >= 0 && e < E_local) atomicOr(&masks[wave * E_local + e], 1ull << lane);
+            }
+        __syncthreads();
+        for (int e = tid; e < E_local; e += PB) {
+            int r = (e > 0 ? tot[e - 1] : 0) + hist[b * E_local + e];  // tot is the inclusive scan
+#pragma unroll
+            for (int ww = 0; ww < PW; ++ww) {
+                wbase[ww * E_local + e] = r;
+                r += __popcll(masks[ww * E_local + e]);
+            }
+        }
+        __syncthreads();
+        if (t < T) {
+            const unsigned long long below = (1ull << lane) - 1ull;
+            for (int j = 0; j < k; ++j) {
+                const int e = idx[(size_t)t * k + j] - e_lo;
+                int r = -1;
+                if (e >= 0 && e < E_local) {
+                    r = wbase[wave * E_local + e] + __popcll(masks[wave * E_local + e] & below);
+                    tok_of[r] = t;
+                }
+                row_of[(size_t)t * k + j] = r;
+            }
+        }
+        __syncthreads();  // masks and wbase are rewritten for the next block
+    }
+}
+
 hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
                           int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st) {
     int nblk = (T + PB - 1) / PB;
+    if (nblk <= PF_BLOCKS) {
+        hipLaunchKernelGGL(permute_fused_kernel, dim3(1), dim3(PB), 0, st, idx, T, k, e_lo, E_local, offsets, row_of,
+                           tok_of);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(permute_hist_kernel, dim3(nblk), dim3(PB), E_local * sizeof(int32_t), st, idx, T, k,
                        e_lo, E_local, blockhist);
     hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(256), 0, st, blockhist, nblk, E_local, offsets);

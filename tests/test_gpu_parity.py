@@ -130,6 +130,9 @@ PERM_CASES = [
     ("ep_share", 600, 256, 8, 64, 32),
     ("one_local", 300, 16, 4, 9, 1),
     ("single_token", 1, 8, 2, 0, 8),
+    ("two_blocks_one_kernel", 512, 64, 6, 0, 64),
+    ("three_blocks_three_kernels", 513, 64, 6, 0, 64),
+    ("nine_blocks", 2049, 64, 6, 0, 64),
 ]
 
 
