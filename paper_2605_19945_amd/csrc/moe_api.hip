@@ -181,6 +181,7 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     c->ev_count = 0;
     c->last_cls = -1;
     c->forced_cls = -1;
+    c->table_r_T = -1;
     // the resident router's ticket counter must be zero before the first launch (each launch leaves
     // it at zero again); synchronous, creation is not on the hot path
     if (note_hip(hipMemset(c->route_ws, 0, (size_t)MOE_ROUTE_WS_INTS * 4), "hipMemset(workspace)") != MOE_OK) {
@@ -258,7 +259,7 @@ moe_status moe_route(moe_ctx* c, const void* x, const void* rp, const float* bia
     if (bias != nullptr && !aligned(bias, 4)) return MOE_ERR_INVALID_ARG;
     if (T == 0) return MOE_OK;
     return from_hip(launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, c->s.d, c->s.E, c->s.k,
-                                 topk_idx, topk_w, counts, c->logits, logits_slabs(c, T), c->table_r, c->route_ws,
+                                 topk_idx, topk_w, counts, c->logits, logits_slabs(c, T), c->table_r, &c->table_r_T, c->route_ws,
                                  (hipStream_t)stream));
 }
 
@@ -378,7 +379,7 @@ moe_status moe_layer_forward(moe_ctx* c, const void* x, const void* rp, const fl
 
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_ROUTE], st);
     hipError_t e = launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, s.d, s.E, s.k, c->idx, c->w,
-                                counts, c->logits, logits_slabs(c, T), c->table_r, c->route_ws, st);
+                                counts, c->logits, logits_slabs(c, T), c->table_r, &c->table_r_T, c->route_ws, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_PERMUTE], st);
     e = launch_permute(c->idx, T, s.k, s.e_lo, s.E_local, c->blockhist, c->offsets, c->row_of, c->tok_of, st);

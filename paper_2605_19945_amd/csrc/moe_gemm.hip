@@ -406,17 +406,22 @@ int router_gemm_grid_max(int T_max, int Rp) {
     return g;
 }
 
+// *table_T: the token count the work list in `table` was last built for (it depends on nothing else for a
+// given context), so that steps with an unchanged batch size skip that launch.
 hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
-                              int max_split, int* nsplit_out, TileDesc* table, hipStream_t st) {
+                              int max_split, int* nsplit_out, TileDesc* table, int* table_T, hipStream_t st) {
     const RouterPick pk = router_gemm_pick(T, d, Rp, max_split);
     const int c = pk.cls;
     const int nt = (Rp + GEMM_BN - 1) / GEMM_BN;
     const int grid = sched_grid(T / (32 * sched_min_cap_blocks(kClassRows[c])) + 1, nt);
     *nsplit_out = pk.nsplit;
-    hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
-                       kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T);
-    hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
+    if (*table_T != T) {
+        hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
+                           kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        *table_T = T;
+    }
     return gemm_launch_pairsum(c, grid, x, d, nullptr, rp, Rp, d / pk.nsplit, (uint16_t*)logits, ldl, table, pk.nsplit,
                                (size_t)T * ldl * sizeof(float), st);
 }

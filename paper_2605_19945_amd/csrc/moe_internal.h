@@ -48,6 +48,7 @@ struct moe_ctx {
     TileDesc* table1;    // [grid1_max]
     TileDesc* table2;    // [grid2_max]
     TileDesc* table_r;   // router GEMM work list (E >= MOE_ROUTER_GEMM_MIN_E)
+    int table_r_T;       // token count table_r was built for, -1: none yet
     float* logits;       // [T_max, router cols] fp32 (E >= MOE_ROUTER_GEMM_MIN_E)
     int32_t* route_ws;   // [MOE_ROUTE_WS_INTS] resident router: ticket (zero between launches) + partial counts
     uint16_t* H;         // [rows_cap, f] bf16
@@ -96,7 +97,7 @@ hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uin
                                int d, int f, uint16_t* packed, hipStream_t st);
 hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias, int T, int d, int E,
                         int k, int32_t* idx, float* w, int32_t* counts, float* logits_ws, int logits_slabs,
-                        TileDesc* table_ws, int32_t* route_ws, hipStream_t st);
+                        TileDesc* table_ws, int* table_T, int32_t* route_ws, hipStream_t st);
 hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
                           int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st);
 hipError_t launch_gather(const uint16_t* x, const int32_t* row_of, int T, int k, int d, uint16_t* xp,
@@ -110,7 +111,7 @@ int gemm_class_rows(int cls);
 hipError_t gemm_init_attributes();
 int router_gemm_grid_max(int T_max, int Rp);
 hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
-                              int max_split, int* nsplit_out, TileDesc* table, hipStream_t st);
+                              int max_split, int* nsplit_out, TileDesc* table, int* table_T, hipStream_t st);
 // Slabs of partial router logits ([T, cols] fp32 each) the workspace holds for T tokens
 static inline int moe_router_split_cap(int T) { return T <= 8192 ? 8 : T <= 16384 ? 4 : T <= 32768 ? 2 : 1; }
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,

@@ -428,7 +428,7 @@ static hipError_t route_launch_t(const uint16_t* x, const uint16_t* rp, const fl
 
 hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias, int T, int d, int E, int k,
                         int32_t* idx, float* w, int32_t* counts, float* logits_ws, int logits_slabs,
-                        TileDesc* table_ws, int32_t* route_ws, hipStream_t st) {
+                        TileDesc* table_ws, int* table_T, int32_t* route_ws, hipStream_t st) {
     if (moe_router_resident(E, d)) {
         const int groups = (T + ROUTE_TOK - 1) / ROUTE_TOK;
         const int grid = groups < RR_MAX_GRID ? groups : RR_MAX_GRID;
@@ -441,7 +441,7 @@ hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias
         // logits on the tiled GEMM kernel (reduction over d, two bf16 terms of Wg), then top-k
         const int Ep = moe_router_cols(E);
         int nsplit = 1;
-        err = launch_router_gemm(x, rp, T, d, 2 * Ep, logits_ws, Ep, logits_slabs, &nsplit, table_ws, st);
+        err = launch_router_gemm(x, rp, T, d, 2 * Ep, logits_ws, Ep, logits_slabs, &nsplit, table_ws, table_T, st);
         if (err != hipSuccess) return err;
         const int blocks = (T + 3) / 4;
         const int epl = (E + 63) / 64;
