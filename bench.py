@@ -226,6 +226,8 @@ def main():
     ap.add_argument("--tile-class", type=int, default=-1)
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="also measure the bf16 MFMA rate the device sustains under an MFMA-only load")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for HBM byte counters)")
     ap.add_argument("--profile-curve", action="store_true",
@@ -301,6 +303,12 @@ def main():
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_tokens)
+    if args.mfma_ceiling:
+        # context for roofline.frac, not a replacement of the published peak it is computed against
+        sustained = moe.moe_measure_mfma_rate(2500, 5)
+        log(f"sustained MFMA-only rate: {sustained:.0f} TFLOP/s = {100 * sustained / PEAK_BF16_TFLOPS:.1f} % of the "
+            f"{PEAK_BF16_TFLOPS:.0f} TFLOP/s peak; GEMM1 reaches {100 * g1 / sustained:.1f} % of it")
+        result["roofline"]["sustained_mfma_only"] = sustained
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)

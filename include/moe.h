@@ -196,6 +196,14 @@ moe_status moe_gem_place(const int32_t* trace, int32_t S, int32_t E, int32_t G, 
  * for tuning runs; -1: choose from the expected rows per expert, the default). */
 moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
 
+/* Measurement aid for roofline reports: the bf16 matrix-core rate this device SUSTAINS under a load of
+ * nothing but v_mfma_f32_32x32x16_bf16 on changing pseudo-random operands (no memory traffic, every SIMD
+ * of every compute unit busy, independent accumulators), in TFLOP/s.  The published peak assumes the
+ * maximum clock; under a dense MFMA load the chip runs at the clock its power limit allows.  Runs
+ * `launches` >= 1 launches of iters_per_wave * 64 MFMAs per wavefront on `stream`, times them with events and waits for them.
+ * tflops: host pointer.  Errors: MOE_ERR_INVALID_ARG, MOE_ERR_DEVICE. */
+moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops /* host */, void* stream);
+
 /* Device pointers into the workspace holding the intermediates of the most recent
  * moe_layer_forward: topk_idx [T,k], topk_w [T,k], offsets [E_local+1], row_of [T,k]. */
 moe_status moe_layer_intermediates(moe_ctx* ctx, const int32_t** topk_idx, const float** topk_w,

@@ -13,4 +13,5 @@ from .binding import (  # noqa: F401
     FLAG_STAGE_EVENTS,
     moe_gem_score,
     moe_gem_place,
+    moe_measure_mfma_rate,
 )

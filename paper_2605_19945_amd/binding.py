@@ -59,6 +59,7 @@ _SIGNATURES = {
     "moe_gem_score": (C.c_int, [_VP, _I32, _I32, _I32, _VP, _VP, _VP, _VP, C.POINTER(C.c_double)]),
     "moe_gem_place": (C.c_int, [_VP, _I32, _I32, _I32, _VP, _VP, _VP, _VP, _I32, _VP, C.POINTER(C.c_double),
                                 C.POINTER(_I32)]),
+    "moe_measure_mfma_rate": (C.c_int, [_I32, _I32, C.POINTER(C.c_float), _VP]),
     "moe_tile_rows": (_I32, [_VP]),
     "moe_set_tile_class": (C.c_int, [_VP, _I32]),
     "moe_layer_intermediates": (C.c_int, [_VP, C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP)]),
@@ -259,6 +260,17 @@ def _curve_arrays(curves):
     off = np.zeros(len(curves) + 1, dtype=np.int32)
     off[1:] = np.cumsum([len(c) for c, _ in curves])
     return counts, ms, off
+
+
+def moe_measure_mfma_rate(iters_per_wave=2500, launches=5):
+    """Sustained bf16 MFMA rate (TFLOP/s) of the current device under an MFMA-only load."""
+    import torch
+    lib = load_library()
+    out = C.c_float()
+    st = lib.moe_measure_mfma_rate(iters_per_wave, launches, C.byref(out), torch.cuda.current_stream().cuda_stream)
+    if st != 0:
+        raise MoEError(st, "moe_measure_mfma_rate")
+    return out.value
 
 
 def moe_gem_score(trace, curves, mapping):

@@ -218,6 +218,30 @@ void moe_destroy(moe_ctx* c) {
     delete c;
 }
 
+moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops, void* stream) {
+    if (tflops == nullptr || iters_per_wave < 1 || launches < 1) return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (note_hip(hipEventCreate(&e0), "hipEventCreate") != MOE_OK) return MOE_ERR_DEVICE;
+    if (note_hip(hipEventCreate(&e1), "hipEventCreate") != MOE_OK) {
+        (void)hipEventDestroy(e0);
+        return MOE_ERR_DEVICE;
+    }
+    double flop = 0;
+    moe_status rc = note_hip(launch_mfma_rate(iters_per_wave, &flop, st), "mfma_rate_kernel");  // warm-up
+    if (rc == MOE_OK) rc = note_hip(hipEventRecord(e0, st), "hipEventRecord");
+    for (int i = 0; i < launches && rc == MOE_OK; ++i)
+        rc = note_hip(launch_mfma_rate(iters_per_wave, &flop, st), "mfma_rate_kernel");
+    if (rc == MOE_OK) rc = note_hip(hipEventRecord(e1, st), "hipEventRecord");
+    if (rc == MOE_OK) rc = note_hip(hipEventSynchronize(e1), "hipEventSynchronize");
+    float ms = 0.f;
+    if (rc == MOE_OK) rc = note_hip(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime");
+    if (rc == MOE_OK) *tflops = ms > 0.f ? (float)(flop * launches / (ms * 1e9)) : 0.f;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
+
 moe_status moe_set_tile_class(moe_ctx* c, int32_t cls) {
     if (c == nullptr || cls < -1 || cls >= GEMM_NUM_CLASSES) return MOE_ERR_INVALID_ARG;
     c->forced_cls = cls;

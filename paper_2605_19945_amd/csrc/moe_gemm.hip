@@ -425,3 +425,48 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
     return gemm_launch_pairsum(c, grid, x, d, nullptr, rp, Rp, d / pk.nsplit, (uint16_t*)logits, ldl, table, pk.nsplit,
                                (size_t)T * ldl * sizeof(float), st);
 }
+
+// ---- sustained matrix-core rate (measurement aid) ------------------------------------------------
+// Every wavefront issues iters * 64 MFMAs on 8 independent accumulator blocks and touches no memory until
+// its single predicated store; 4 wavefronts per workgroup, 8 workgroups per compute unit in the grid.
+// The operands are 8 + 8 registers of pseudo-random bf16 values (random sign and mantissa, magnitudes
+// 0.5 .. 2) paired differently in every MFMA, so that the multipliers see changing inputs as they do in a
+// GEMM: with constant operands the same kernel runs at the full 2.4 GHz, with these it does not.
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ sink, int iters) {
+    const uint32_t lane = threadIdx.x & 63;
+    bf16x8_t a[8], b[8];
+    uint32_t h = lane * 0x9E3779B1u + 0x7F4A7C15u;
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            h = h * 1664525u + 1013904223u;
+            // sign | exponent 126 or 127 | 7 mantissa bits
+            a[r][i] = __builtin_bit_cast(__bf16, (uint16_t)(((h >> 16) & 0x8000u) | ((126u + ((h >> 8) & 1u)) << 7) | ((h >> 20) & 0x7Fu)));
+            h = h * 1664525u + 1013904223u;
+            b[r][i] = __builtin_bit_cast(__bf16, (uint16_t)(((h >> 16) & 0x8000u) | ((126u + ((h >> 8) & 1u)) << 7) | ((h >> 20) & 0x7Fu)));
+        }
+    f32x16_t acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + u) & 7], acc[j], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += acc[j][j];
+    if (s == 1.2345e-30f) sink[blockIdx.x * 256 + threadIdx.x] = s;  // practically never: keeps the sums live
+}
+
+hipError_t launch_mfma_rate(int iters_per_wave, double* flop, hipStream_t st) {
+    const int grid = SCHED_CU * 8;
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, st, (float*)nullptr, iters_per_wave);
+    *flop = (double)grid * 4 * (double)iters_per_wave * 64 * (2.0 * 32 * 32 * 16);
+    return hipGetLastError();
+}

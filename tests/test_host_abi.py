@@ -86,6 +86,7 @@ def test_create_and_call_validation_without_device(lib):
     assert lib.moe_pack_weights(None, p, p, p, p, None) == 1
     assert lib.moe_stage_times(None, None) == 1
     assert lib.moe_set_tile_class(None, 0) == 1
+    assert lib.moe_measure_mfma_rate(0, 1, None, None) == 1     # rejected before any device call
     assert lib.moe_tile_rows(None) == 0
     lib.moe_destroy(None)                                                          # no-op
 
