@@ -45,13 +45,16 @@
 
 #include "moe_internal.h"
 
+// two floats rounded to nearest even and packed, a in the low half: one v_cvt_pk_bf16_f32
 static __device__ inline uint32_t pack2_bf16(float a, float b) {
-    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-    ua += 0x7FFFu + ((ua >> 16) & 1u);
-    ub += 0x7FFFu + ((ub >> 16) & 1u);
-    return (ua >> 16) | (ub & 0xFFFF0000u);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
-static __device__ inline float silu_f32(float g) { return g / (1.f + __expf(-g)); }
+// g * sigmoid(g) with the hardware reciprocal (1 ulp): an IEEE division costs about ten more instructions
+// per element, 144 elements per lane and tile, all of them after the last MFMA
+static __device__ inline float silu_f32(float g) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)); }
 
 enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_PAIR_SUM_F32 = 2, EPI_PARTIAL_F32 = 3 };
 
