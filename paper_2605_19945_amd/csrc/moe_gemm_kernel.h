@@ -513,13 +513,24 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
 // Classes 0 and 1 are the production token-tile classes (row tiles of up to 128 rows for very low
 // loads, up to 288 rows otherwise); higher ids are alternatives kept for tuning runs
 // (moe_set_tile_class).
+// A unit that defines MOE_GEMM_NO_TALL_TILE before including this file leaves out the 288-row class (its
+// launcher then rejects class 1): the router-logit GEMM never uses it, and with that unit's epilogue the
+// compiler copies the VGPR accumulators right behind their MFMAs (see mfma_pinned_vgpr).
 //   V(id, BM, NSX)
+#ifdef MOE_GEMM_NO_TALL_TILE
+#define FOR_EACH_VARIANT(V) \
+    V(0, 128, 4)            \
+    V(2, 64, 4)             \
+    V(3, 32, 4)             \
+    V(4, 256, 4)
+#else
 #define FOR_EACH_VARIANT(V) \
     V(0, 128, 4)            \
     V(1, 288, 4)            \
     V(2, 64, 4)             \
     V(3, 32, 4)             \
     V(4, 256, 4)
+#endif
 
 template <int BM, int NSX, int EPI>
 struct Variant {

@@ -112,7 +112,7 @@ def test_lint_flags_an_early_reader():
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="no hipcc")
 def test_no_reader_follows_a_vgpr_accumulating_mfma_too_closely(tmp_path):
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    units = ["moe_gemm_swiglu.hip", "moe_gemm_plain.hip"]
+    units = ["moe_gemm_swiglu.hip", "moe_gemm_plain.hip", "moe_gemm_partial.hip", "moe_gemm_pairsum.hip"]
 
     def compile_one(src):
         out = str(tmp_path / src.replace(".hip", ".s"))
@@ -126,5 +126,8 @@ def test_no_reader_follows_a_vgpr_accumulating_mfma_too_closely(tmp_path):
     for out in outs:
         with open(out) as fh:
             pinned, bad = find_hazards(fh.read().splitlines())
-        assert pinned > 0, f"{out}: expected MFMAs with a VGPR destination (the ninth row block of the 288-row tile)"
+        if out.endswith("pairsum.s"):
+            assert pinned == 0, f"{out}: the router-logit unit is built without the 288-row tile"
+        else:
+            assert pinned > 0, f"{out}: expected MFMAs with a VGPR destination (the ninth row block of the 288-row tile)"
         assert not bad, f"{out}:\n" + "\n".join(bad[:10])
