@@ -228,6 +228,37 @@ def test_grouped_ffn_parity(moe, case):
     ctx.close()
 
 
+def test_grouped_ffn_random_shapes(moe):
+    """Seeded sweep over expert counts, widths (weight-row tiles that do not divide by 8, short and long
+    reductions), loads from a few rows to thousands, skew with empty experts, and tile classes: every
+    row must be written exactly as the oracle has it, whatever work list the device builds."""
+    import torch
+    rng = np.random.default_rng(2605)
+    for case in range(24):
+        E_local = int(rng.choice([1, 2, 3, 5, 8, 13, 24, 48]))
+        d = int(rng.choice([64, 128, 192, 320, 512]))
+        f = int(rng.choice([64, 128, 256, 448, 1024, 2048]))
+        total = int(rng.choice([1, 7, 33, 150, 700, 2500, 6000]))
+        while total * d * f > 1.2e9:
+            total //= 2
+        cls = int(rng.choice([-1, -1, 0, 1, 4]))
+        off = ragged_offsets(rng, E_local, total, empty_frac=float(rng.choice([0.0, 0.3, 0.7])))
+        print(f"random ffn case {case}: E_local={E_local} d={d} f={f} rows={total} class={cls} "
+              f"max rows/expert={int(np.diff(off).max())}", flush=True)
+        W1, W3, W2 = wl.expert_weights(100 + case, E_local, d, f, 0.08)
+        xp = wl.gaussian_bf16_bits(100 + case, 9, (total, d), 1.0)
+        ctx = moe.MoEContext(total, d, f, E_local, 1)
+        packed = ctx.moe_pack_weights(gu.to_dev_bf16(W1), gu.to_dev_bf16(W3), gu.to_dev_bf16(W2))
+        ctx.moe_set_tile_class(cls)
+        y = torch.full((total, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ctx.moe_grouped_ffn(gu.to_dev_bf16(xp), gu.to_dev(off), total, packed, y=y)
+        torch.cuda.synchronize()
+        got = gu.f64_of_bf16(y)
+        assert np.isfinite(got).all(), f"case {case}: rows were left unwritten"
+        gu.check_output(got, orc.grouped_ffn(xp, off, W1, W3, W2), what=f"random case {case}")
+        ctx.close()
+
+
 def test_grouped_ffn_all_rows_in_one_expert_and_rows_cap_larger_than_used(moe):
     import torch
     E_local, d, f, cap, used = 4, 128, 128, 600, 333
