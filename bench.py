@@ -81,6 +81,29 @@ def time_layer(ctx, x, rp, bias, packed, out, steps, warmup):
     return dt / steps * 1e3, ctx.moe_stage_times()
 
 
+def time_layer_graph(moe, s, x, rp, bias, packed, out, steps, warmup):
+    """The same layer call captured once into a HIP graph and replayed (a context without stage events:
+    those record events into the stream)."""
+    import torch
+    ctx = moe.MoEContext(s.T, s.d, s.f, s.E, s.k, s.e_lo, s.E_local)
+    ctx.moe_layer_forward(x, rp, bias, packed, out=out)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.moe_layer_forward(x, rp, bias, packed, out=out)
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    del graph
+    ctx.close()
+    return dt / steps * 1e3
+
+
 def cpu_baseline(inp, sample_tokens):
     """The oracle as it stands, on a bounded sample of the workload's tokens, on the host cores."""
     import numpy as np
@@ -226,6 +249,8 @@ def main():
     ap.add_argument("--tile-class", type=int, default=-1)
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the layer call captured into a HIP graph and replayed")
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="also measure the bf16 MFMA rate the device sustains under an MFMA-only load")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -303,6 +328,10 @@ def main():
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_tokens)
+    if args.graph:
+        gms = time_layer_graph(moe, s, x, rp, bias, packed, out, args.steps, args.warmup)
+        log(f"graph replay {gms:.3f} ms/step ({100 * (gms / ms - 1):+.1f} % against the eager calls)")
+        result["graph_replay_ms_per_step"] = gms
     if args.mfma_ceiling:
         # context for roofline.frac, not a replacement of the published peak it is computed against
         sustained = moe.moe_measure_mfma_rate(2500, 5)

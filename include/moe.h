@@ -21,6 +21,10 @@
  *   - Errors are return codes.  Arguments are validated on the host before any launch; a call
  *     that returns an error has launched nothing.  T == 0 is MOE_OK and a no-op.
  *   - Calls on one moe_ctx must not overlap in time (they share its workspace).
+ *   - The calls that take a stream only launch kernels on it (no memsets, no allocation, no host
+ *     synchronisation), so they may be recorded under stream capture and replayed as a HIP graph; the
+ *     exceptions are contexts created with MOE_FLAG_STAGE_EVENTS (they record events), moe_profile_ffn
+ *     and moe_measure_mfma_rate (they time and wait).
  */
 #ifndef MOE_H_
 #define MOE_H_

@@ -415,12 +415,17 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
     const int nt = (Rp + GEMM_BN - 1) / GEMM_BN;
     const int grid = sched_grid(T / (32 * sched_min_cap_blocks(kClassRows[c])) + 1, nt);
     *nsplit_out = pk.nsplit;
+    // Under stream capture the launch goes into the graph, and a replay may then rebuild the list at any
+    // later time: from the first captured call on, the list is rebuilt by every call (-2 = never skip).
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &capture) != hipSuccess) return hipGetLastError();
+    if (capture != hipStreamCaptureStatusNone) *table_T = -2;
     if (*table_T != T) {
         hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
                            kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
-        *table_T = T;
+        if (*table_T != -2) *table_T = T;
     }
     return gemm_launch_pairsum(c, grid, x, d, nullptr, rp, Rp, d / pk.nsplit, (uint16_t*)logits, ldl, table, pk.nsplit,
                                (size_t)T * ldl * sizeof(float), st);

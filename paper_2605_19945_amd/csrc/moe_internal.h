@@ -48,7 +48,7 @@ struct moe_ctx {
     TileDesc* table1;    // [grid1_max]
     TileDesc* table2;    // [grid2_max]
     TileDesc* table_r;   // router GEMM work list (E >= MOE_ROUTER_GEMM_MIN_E)
-    int table_r_T;       // token count table_r was built for, -1: none yet
+    int table_r_T;       // token count table_r was built for; -1: none yet; -2: rebuild at every call
     float* logits;       // [T_max, router cols] fp32 (E >= MOE_ROUTER_GEMM_MIN_E)
     int32_t* route_ws;   // [MOE_ROUTE_WS_INTS] resident router: ticket (zero between launches) + partial counts
     uint16_t* H;         // [rows_cap, f] bf16

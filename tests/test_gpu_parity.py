@@ -464,3 +464,41 @@ def test_sustained_mfma_rate_is_plausible(moe):
     rate = moe.moe_measure_mfma_rate(300, 2)
     print(f"   sustained MFMA-only rate {rate:.0f} TFLOP/s", flush=True)
     assert 600.0 < rate < 2600.0
+
+
+@pytest.mark.parametrize("which", ["resident_router", "gemm_router"])
+def test_layer_forward_under_graph_capture(moe, which):
+    """moe_layer_forward records kernel launches only, so a caller may capture it into a HIP graph: every
+    replay, with new inputs in the captured buffers and eager calls of another batch size in between,
+    must reproduce the eager result bit for bit."""
+    import torch
+    if which == "resident_router":
+        mk = lambda T, seed: wl.custom("g", T, 512, 256, 8, 2, seed=seed, wg_std=0.05, w_std=0.06)
+    else:
+        mk = lambda T, seed: wl.custom("g", T, 256, 128, 64, 4, seed=seed, wg_std=0.05, w_std=0.06)
+    T = 96
+    base = mk(T, 0)
+    s = base.shape
+    ctx = moe.MoEContext(2 * T, s.d, s.f, s.E, s.k)
+    rp = ctx.moe_pack_router(gu.to_dev(base.Wg))
+    packed = ctx.moe_pack_weights(gu.to_dev_bf16(base.W1), gu.to_dev_bf16(base.W3), gu.to_dev_bf16(base.W2))
+    x_buf = gu.to_dev_bf16(base.x).clone()
+    out_buf = torch.empty((T, s.d), dtype=torch.bfloat16, device="cuda")
+    ctx.moe_layer_forward(x_buf, rp, None, packed, out=out_buf)          # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.moe_layer_forward(x_buf, rp, None, packed, out=out_buf)
+    other = gu.to_dev_bf16(mk(2 * T, 7).x)
+    for rep in range(3):
+        x_new = gu.to_dev_bf16(mk(T, 10 + rep).x)
+        eager = ctx.moe_layer_forward(x_new, rp, None, packed).clone()
+        ctx.moe_layer_forward(other, rp, None, packed)                   # another batch size in between
+        torch.cuda.synchronize()
+        x_buf.copy_(x_new)
+        out_buf.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_buf.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager call"
+    del graph
+    ctx.close()
