@@ -10,7 +10,7 @@ CPU oracle timed on a bounded sample of the same workload on this machine's host cor
 
 `--curve` additionally sweeps the skewed Mixtral-shaped workload over token loads and writes the
 latency-vs-token-load table (the per-GPU profile the paper's mapping search consumes, Sec. 3.3.2)
-to gpurun_out/latency_curve.json.
+to latency_curve.json in the output folder (--out-dir).
 """
 import argparse
 import json
@@ -28,6 +28,9 @@ PEAK_HBM_GBS = 8000.0
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+OUT_DIR_DEFAULT = "bench_out"
 
 
 def make_workload(name, seed, weights):
@@ -148,14 +151,14 @@ def run_curve(moe, gu, weights_dev_packed, args):
                      "expert_counts": counts.cpu().tolist(), "stages_ms": stages})
         log(f"curve T={T}: {ms:.3f} ms  {flops / ms / 1e9:.1f} TFLOP/s  counts={counts.cpu().tolist()}")
     ctx.close()
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "latency_curve.json"), "w") as fh:
+    os.makedirs(os.path.join(ROOT, args.out_dir), exist_ok=True)
+    with open(os.path.join(ROOT, args.out_dir, "latency_curve.json"), "w") as fh:
         json.dump({"workload": "mixtral_skewed", "rows": rows}, fh, indent=1)
 
 
 def run_profile_curve(moe, s, packed, args):
     """Token-vs-latency curve of the isolated expert kernels, sampled at the tile boundaries
-    (paper Sec. 3.3.2, Step-2) -> gpurun_out/cg_curve.json."""
+    (paper Sec. 3.3.2, Step-2) -> cg_curve.json in the output folder."""
     import torch
     from paper_2605_19945_amd import latency_curve as lc
     boundary = s.E_local * 32            # row tiles grow in steps of 32 rows per expert
@@ -186,8 +189,8 @@ def run_profile_curve(moe, s, packed, args):
         f"change across the rest of a step (m*{boundary}+{after} -> (m+1)*{boundary}): median {100 * sorted(flat)[len(flat) // 2]:.1f} %")
     for n in (1, boundary, boundary + after, 1024, 4096, 8192, dense_max, n_max):
         log(f"   C_g({n}) = {curve.at(n):.3f} ms")
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "cg_curve.json"), "w") as fh:
+    os.makedirs(os.path.join(ROOT, args.out_dir), exist_ok=True)
+    with open(os.path.join(ROOT, args.out_dir, "cg_curve.json"), "w") as fh:
         json.dump({"boundary": boundary, "after": after, "dense_end": dense_end, "iters": args.profile_iters,
                    "counts": counts, "ms": ms, "profiling_kernel_ms": cost, "full_sweep_kernel_ms": sweep}, fh)
     ctx.close()
@@ -249,6 +252,7 @@ def main():
     ap.add_argument("--tile-class", type=int, default=-1)
     ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--out-dir", default=OUT_DIR_DEFAULT, help="folder (under the repo root) for the curve JSON files")
     ap.add_argument("--graph", action="store_true",
                     help="also time the layer call captured into a HIP graph and replayed")
     ap.add_argument("--mfma-ceiling", action="store_true",

@@ -9,7 +9,7 @@ of E experts for every token, the token is sent to those experts, each expert is
 network, and the per-expert token counts fall out of the router (Sec. 3.3.1, Step 1).  It prints
 no formula and no worked example of the layer.  The formulas below are therefore the standard
 definition named by the build target (softmax over the k selected logits, SwiGLU experts
-W2^T(silu(W1^T x) * W3^T x), no biases in the experts); every reading is listed in the design doc.
+W2^T(silu(W1^T x) * W3^T x), no biases in the experts).
 
 Arithmetic: inputs are bf16 bit patterns or fp32, widened exactly to fp64; all sums are fp64
 (numpy matmul is the contraction primitive).  Router logits are rounded once to fp32 and every
