@@ -310,14 +310,14 @@ static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t*
     c->last_cls = cls;
     const uint16_t* w13f = packed;
     const uint16_t* w2f = packed + (size_t)s.E_local * 2 * s.f * s.d;
-    hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, st);
+    // offsets[E_local] = the rows actually present
+    const int nsplit = gemm_pick_split2(p, n_rows_cap, s.E_local, s.d, s.f, c->part_bytes);
+    hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, nsplit, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM1], st);
     e = launch_gemm1(p, X, s.d, row_map, w13f, s.d, s.f, c->H, c->table1, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM2], st);
-    // offsets[E_local] = the rows actually present
-    const int nsplit = gemm_pick_split2(p, n_rows_cap, s.E_local, s.d, s.f, c->part_bytes);
     e = launch_gemm2(p, c->H, w2f, s.d, s.f, Y, c->table2, nsplit, c->part, n_rows_cap, offsets + s.E_local, st);
     return from_hip(e);
 }

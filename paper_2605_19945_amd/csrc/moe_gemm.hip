@@ -7,12 +7,14 @@
 // equal height (a multiple of 32 rows, at most cap): an expert slightly larger than a multiple of
 // the cap does not get a nearly empty extra tile, its rows are spread over its tiles.
 //
-// The cap itself is chosen per GEMM from {bm, bm-32, ..., ~5/8 bm} on the device, from the actual
+// The cap itself is chosen per GEMM on the device from the tallest tile and the next five heights down
+// (as far as their row tiles fit the work list), from the actual
 // loads: a launch runs in ceil(work items / compute units) rounds of roughly one tile time each, so
 // when there are only a few rounds (the second expert GEMM has few weight-row tiles) a slightly
 // lower cap that fills the last round beats the tallest tile -- the tile-boundary staircase of
 // Sec. 3.3.2, seen from the scheduler's side.  Estimated time of a cap, in units of one 32-row
-// block of MFMA work: rounds * (mean tile height in blocks + SCHED_TILE_OVERHEAD).
+// block of MFMA work: rounds * (mean tile height in blocks + SCHED_TILE_OVERHEAD); a launch with reduction
+// splits has that many workgroups per work item.
 //
 // Order of the work list.  The hardware hands out the workgroups of a launch in index order:
 // workgroup b goes to XCD b % 8, and within an XCD to shader engine (b / 8) % 4, whose eight compute
@@ -41,12 +43,18 @@ constexpr int SCHED_PIECE_MAX = 8;  // row tiles per piece, at most
 // further the workgroups drift apart -- and 3.5 picks caps that are as fast or up to 2 % faster than
 // those picked with 1.0 on every benchmark workload.
 constexpr float SCHED_TILE_OVERHEAD = 3.5f;
-static __host__ __device__ inline int sched_min_cap_blocks(int bm) { return (5 * (bm / 32) + 7) / 8; }
-// Entries of a work list (= workgroups of the launch): eight times the longest XCD queue must fit.
-// The queues together hold (row tiles * weight-row tiles) entries; dealing whole pieces can leave them
-// unequal, and the scheduler falls back to single-tile pieces, whose queues differ by at most one
-// entry, when the longest one would not fit.
-static inline int sched_grid(int mt_max, int nt) { return 2 * mt_max * nt + 8 * SCHED_PIECE_MAX; }
+constexpr int SCHED_CAPS = 6;  // candidate caps: the tallest tile and the next five heights down
+static __host__ __device__ inline int sched_min_cap_blocks(int bm) {
+    const int h = bm / 32 - (SCHED_CAPS - 1);
+    return h < 1 ? 1 : h;
+}
+// Entries of a work list (= workgroups of the launch) for at most mt row tiles: the eight queues together
+// hold (row tiles * weight-row tiles) entries; dealing whole pieces can leave them unequal, and the
+// scheduler falls back to single-tile pieces, whose queues differ by at most one entry, when eight times
+// the longest would not fit.  Workgroups past the end of their queue exit at once, but each still has to
+// be placed on a compute unit with its full LDS and register allotment (about 0.5 us): the list is kept
+// as short as the bound allows.
+static inline int sched_grid(int mt, int nt) { return mt * nt + 64; }
 
 // inclusive prefix sum over the 64 lanes with data-parallel-primitive moves: a Kogge-Stone scan inside
 // each row of 16 lanes, then the row totals are carried into the following rows
@@ -81,14 +89,15 @@ static __device__ inline int sched_count_mod8(int a, int len, int x) {
 __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict__ offsets, int E_local,
                                                        int bm, int bn, int nt1, int grid1,
                                                        TileDesc* __restrict__ t1, int nt2, int grid2,
-                                                       TileDesc* __restrict__ t2, int host_rows) {
+                                                       TileDesc* __restrict__ t2, int host_rows, int nsplit1,
+                                                       int nsplit2) {
     __shared__ int32_t s_off[257];
     __shared__ int32_t s_mte[256];     // row tiles of expert e
     __shared__ int32_t s_pre[257];     // pieces per weight-row tile of the experts before e; [E_local] = total
     __shared__ int32_t s_len[8][257];  // tiles in XCD x's queue before those of expert e; [E_local] = length
     __shared__ int32_t s_wave[8][4];
     __shared__ int32_t s_part[4];
-    __shared__ int32_t s_tot[6][4];
+    __shared__ int32_t s_tot[SCHED_CAPS + 2][4];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     // host_rows >= 0: one group of host_rows rows (the router GEMM), no offsets array to read
@@ -99,24 +108,24 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
     }
     for (int i = tid; i <= E_local; i += 256) s_off[i] = host_rows >= 0 ? i * host_rows : offsets[i];
     const int hmax = bm / 32, hmin = sched_min_cap_blocks(bm);
-    // totals over the experts: 32-row blocks, loaded experts, row tiles for every candidate cap (<= 4)
-    int tot[6];
+    // totals over the experts: 32-row blocks, loaded experts, row tiles for every candidate cap
+    int tot[SCHED_CAPS + 2];
     tot[0] = nblk_e;
-    tot[5] = nblk_e > 0 ? 1 : 0;
+    tot[SCHED_CAPS + 1] = nblk_e > 0 ? 1 : 0;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < SCHED_CAPS; ++c) {
         const int h = hmax - c;
         tot[c + 1] = (h >= hmin && nblk_e > 0) ? (nblk_e + h - 1) / h : 0;
     }
     {
 #pragma unroll
-        for (int c = 0; c < 6; ++c) {
+        for (int c = 0; c < SCHED_CAPS + 2; ++c) {
             const int incl = wave_scan_incl(tot[c]);
             if (lane == 63) s_tot[c][wave] = incl;
         }
         __syncthreads();
 #pragma unroll
-        for (int c = 0; c < 6; ++c) tot[c] = s_tot[c][0] + s_tot[c][1] + s_tot[c][2] + s_tot[c][3];
+        for (int c = 0; c < SCHED_CAPS + 2; ++c) tot[c] = s_tot[c][0] + s_tot[c][1] + s_tot[c][2] + s_tot[c][3];
     }
 
     for (int which = 0; which < 2; ++which) {
@@ -127,11 +136,12 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
         // ---- pick the cap --------------------------------------------------------------------
         int cap = hmax, MT = 0;
         float best = 3.0e38f;
+        const int nsplit = which ? nsplit2 : nsplit1;  // reduction splits: workgroups per table entry
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < SCHED_CAPS; ++c) {
             const int tiles = tot[c + 1];
-            if (tiles > 0) {
-                const int rounds = (tiles * nt + SCHED_CU - 1) / SCHED_CU;
+            if (tiles > 0 && (long long)tiles * nt + 8 <= grid) {
+                const int rounds = (tiles * nt * nsplit + SCHED_CU - 1) / SCHED_CU;
                 const float est = (float)rounds * ((float)tot[0] / (float)tiles + SCHED_TILE_OVERHEAD);
                 if (est < best) {  // ties keep the taller tile
                     best = est;
@@ -266,8 +276,10 @@ GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) 
     p.bm = kClassRows[cls];
     p.bn = GEMM_BN;
     int64_t extra = n_rows_cap < E_local ? n_rows_cap : E_local;
-    // upper bound on the row tiles at the lowest cap the scheduler may pick
-    p.mt_max = (int)(n_rows_cap / (32 * sched_min_cap_blocks(p.bm)) + extra);
+    // Row tiles at the tallest cap number at most rows / bm + one per loaded expert; a quarter more lets the
+    // scheduler pick lower caps (it only considers caps whose tiles fit the list).
+    const int64_t mt_tall = n_rows_cap / p.bm + extra + 1;
+    p.mt_max = (int)(mt_tall + mt_tall / 4);
     p.nt1 = (2 * f + p.bn - 1) / p.bn;
     p.nt2 = (d + p.bn - 1) / p.bn;
     p.grid1 = sched_grid(p.mt_max, p.nt1);
@@ -284,13 +296,13 @@ hipError_t gemm_init_attributes() {
 }
 
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1, TileDesc* t2,
-                           hipStream_t st) {
+                           int nsplit2, hipStream_t st) {
     int g = p.grid1 > p.grid2 ? p.grid1 : p.grid2;
     int blocks = (g + 1023) / 1024;
     if (blocks < 1) blocks = 1;
     if (blocks > 64) blocks = 64;
     hipLaunchKernelGGL(schedule_kernel, dim3(blocks), dim3(256), 0, st, offsets, E_local, p.bm, p.bn, p.nt1,
-                       p.grid1, t1, p.nt2, p.grid2, t2, -1);
+                       p.grid1, t1, p.nt2, p.grid2, t2, -1, 1, nsplit2);
     return hipGetLastError();
 }
 
@@ -422,7 +434,7 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
     if (capture != hipStreamCaptureStatusNone) *table_T = -2;
     if (*table_T != T) {
         hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
-                           kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T);
+                           kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T, pk.nsplit, 1);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
         if (*table_T != -2) *table_T = T;

@@ -115,7 +115,7 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
 // Slabs of partial router logits ([T, cols] fp32 each) the workspace holds for T tokens
 static inline int moe_router_split_cap(int T) { return T <= 8192 ? 8 : T <= 16384 ? 4 : T <= 32768 ? 2 : 1; }
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,
-                           TileDesc* t2, hipStream_t st);
+                           TileDesc* t2, int nsplit2, hipStream_t st);
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table,
                         hipStream_t st);
