@@ -124,7 +124,10 @@ moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int
  *   bf16 operands, fp32 accumulation; the intermediate [rows, f] is stored as bf16 in the
  *   workspace.  Experts with no rows cost nothing and their weights are not read.
  * xp, y [n_rows_cap, d] bf16; offsets [E_local+1] (device; values are not read by the host);
- * n_rows_cap: host upper bound on offsets[E_local], at most moe_rows_capacity(shape, T_max). */
+ * n_rows_cap: host upper bound on offsets[E_local], at most moe_rows_capacity(shape, T_max).  The launches
+ * are sized from it (the per-expert counts stay on the device), so a tight bound is cheaper than a loose
+ * one; at low loads (up to 192 rows per expert on average) the second GEMM runs as several reduction
+ * ranges whose fp32 partial sums are added in a fixed order. */
 moe_status moe_grouped_ffn(moe_ctx* ctx, const void* xp, const int32_t* offsets,
                            int32_t n_rows_cap, const void* packed, void* y, void* stream);
 
