@@ -173,14 +173,42 @@ moe_status moe_profile_ffn(moe_ctx* ctx, const void* xp, const void* packed, voi
                            const int32_t* token_counts /* host */, int32_t n_points, int32_t warmup,
                            int32_t iters, float* ms /* host */, void* stream);
 
-/* ---- host-side mapping search (paper Sec. 3.3.3 "Step-3", Eq. 1; appendix Alg. "Initialmapping",
- * "Refine", "Place").  Everything here is HOST memory and runs on the CPU, as in the paper; the
- * inputs are what the GPU path produces: trace[t*E + e] = tokens routed to expert e at step t (the
- * counts_out rows of S consecutive calls) and one token-vs-latency curve per GPU (moe_profile_ffn
- * samples): GPU g's samples are curve_counts / curve_ms [curve_offsets[g], curve_offsets[g+1]),
- * token counts strictly ascending; C_g(n) joins neighbouring samples by straight lines (first
- * sample's value below it, last one's above it, 0 for n <= 0).  E must be a multiple of G: every
- * GPU hosts E / G experts.  mapping[e] = GPU of expert e. -------------------------------------- */
+/* ---- host-side steps (everything below up to moe_gem_place takes HOST pointers and runs on the CPU, as in
+ * the paper; the inputs are what the GPU path produces) ------------------------------------------------- */
+
+/* Sampling plan of the variability profiler (paper Sec. 3.3.2, Step-2: latency jumps at tile boundaries,
+ * so sample there; sample sparsely at high counts).  Token counts to measure, ascending, no duplicates:
+ * 1; every multiple m*boundary up to min(dense_max, n_max) together with m*boundary + after (the first
+ * count at which the jump is complete) where that is <= n_max; then every sparse_step tokens from the last
+ * dense boundary on, below n_max; and n_max.  Requires boundary, sparse_step, n_max >= 1,
+ * 1 <= after <= boundary, dense_max >= 0.  *n_out = number of counts; with cap == 0 nothing is written (size
+ * query); cap < *n_out gives MOE_ERR_WORKSPACE_TOO_SMALL. */
+moe_status moe_curve_sample_counts(int32_t boundary, int32_t dense_max, int32_t n_max, int32_t sparse_step,
+                                   int32_t after, int32_t* counts_out /* [cap] */, int32_t cap, int32_t* n_out);
+
+/* The curve C_g(n) rebuilt from n_samples measured points (counts strictly ascending, ms their latencies;
+ * Sec. 3.3.2: linear interpolation between samples): ms_out[i] = latency at tokens[i] tokens = the straight
+ * line between the neighbouring samples, the first sample's value below it, the last one's above it, 0 for
+ * tokens <= 0.  The mapping search (moe_gem_*) reads its curves the same way. */
+moe_status moe_curve_eval(const int32_t* counts, const double* ms, int32_t n_samples, const int32_t* tokens,
+                          int32_t n_tokens, double* ms_out /* [n_tokens] */);
+
+/* Sum of C_g(n) over n_lo <= n <= n_hi: the kernel time a sweep of every token count would cost, for the
+ * comparison with the sampled profile (Sec. 4.6 of the paper reports that ratio). */
+moe_status moe_curve_sum(const int32_t* counts, const double* ms, int32_t n_samples, int32_t n_lo, int32_t n_hi,
+                         double* sum_out);
+
+/* Statistics of the expert-utilisation trace (paper Sec. 3.3.1, Step-1; Sec. 3.2): trace[t*E + e] = tokens
+ * routed to expert e at step t.  u_out[e] = mean over the S steps.  r_out[a*E + b] = Pearson correlation
+ * coefficient of the loads of experts a and b across the steps (NaN if either load is constant). */
+moe_status moe_trace_mean_utilisation(const int32_t* trace, int32_t S, int32_t E, double* u_out /* [E] */);
+moe_status moe_trace_correlation(const int32_t* trace, int32_t S, int32_t E, double* r_out /* [E*E] */);
+
+/* Mapping search (paper Sec. 3.3.3 "Step-3", Eq. 1; appendix algorithms for the initial mapping, the
+ * refinement and the restarts).  trace as above (the counts_out rows of S consecutive calls); one
+ * token-vs-latency curve per GPU (moe_profile_ffn samples): GPU g's samples are curve_counts / curve_ms
+ * [curve_offsets[g], curve_offsets[g+1]), token counts strictly ascending, read as in moe_curve_eval.
+ * E must be a multiple of G: every GPU hosts E / G experts.  mapping[e] = GPU of expert e. */
 
 /* S(M) = sum over steps of max over GPUs of C_g(tokens routed to GPU g at that step)  (Eq. 1). */
 moe_status moe_gem_score(const int32_t* trace, int32_t S, int32_t E, int32_t G, const int32_t* curve_counts,

@@ -59,6 +59,11 @@ _SIGNATURES = {
     "moe_gem_score": (C.c_int, [_VP, _I32, _I32, _I32, _VP, _VP, _VP, _VP, C.POINTER(C.c_double)]),
     "moe_gem_place": (C.c_int, [_VP, _I32, _I32, _I32, _VP, _VP, _VP, _VP, _I32, _VP, C.POINTER(C.c_double),
                                 C.POINTER(_I32)]),
+    "moe_curve_sample_counts": (C.c_int, [_I32, _I32, _I32, _I32, _I32, _VP, _I32, C.POINTER(_I32)]),
+    "moe_curve_eval": (C.c_int, [_VP, _VP, _I32, _VP, _I32, _VP]),
+    "moe_curve_sum": (C.c_int, [_VP, _VP, _I32, _I32, _I32, C.POINTER(C.c_double)]),
+    "moe_trace_mean_utilisation": (C.c_int, [_VP, _I32, _I32, _VP]),
+    "moe_trace_correlation": (C.c_int, [_VP, _I32, _I32, _VP]),
     "moe_measure_mfma_rate": (C.c_int, [_I32, _I32, C.POINTER(C.c_float), _VP]),
     "moe_tile_rows": (_I32, [_VP]),
     "moe_set_tile_class": (C.c_int, [_VP, _I32]),

@@ -1,41 +1,35 @@
-"""Token-vs-latency curve C_g(n) of one GPU's expert kernels (paper Sec. 3.3.2, "Step-2: Performance
-Variability Profiling"): where to sample, and how the full curve is rebuilt from the samples.
+"""Token-vs-latency curve C_g(n) of one GPU's expert kernels (paper Sec. 3.3.2, Step-2): which token
+counts to sample and how the full curve is rebuilt from the samples.
 
-Latency is a staircase in the token count: it jumps when a tile boundary is crossed.  With n tokens
-spread evenly over E_local resident experts and row tiles that grow in steps of `tile_step` rows,
-the boundaries in per-GPU tokens are the multiples of b = E_local * tile_step, and the jump after
-m*b is complete at m*b + E_local (the first count at which every expert has crossed).  Up to
-`dense_max` tokens every boundary m*b is sampled together with m*b + after (after = E_local), so
-both ends of every jump and of every flat stretch are measured; beyond that the per-tile increase
-is a small fraction of the total, so counts are sampled every `sparse_step` tokens.  The curve is
-rebuilt by joining neighbouring samples with straight lines.
-
-Measuring is `MoEContext.moe_profile_ffn` (HIP path); this module holds only the host-side logic.
+Argument marshalling only: the sampling plan (moe_curve_sample_counts), the curve look-up
+(moe_curve_eval) and the sweep cost (moe_curve_sum) are computed by the native library; the mapping
+search reads its curves through the same native routine.  Measuring the samples is
+`MoEContext.moe_profile_ffn`.
 """
 from __future__ import annotations
 
-import bisect
+import ctypes as C
 from dataclasses import dataclass
 from typing import List, Sequence
 
+import numpy as np
+
+from .binding import MoEError, load_library
+
 
 def sample_counts(boundary: int, dense_max: int, n_max: int, sparse_step: int, after: int = 1) -> List[int]:
-    """Token counts to measure: 1, every m*boundary and m*boundary + after up to dense_max, then
-    every sparse_step tokens up to n_max (n_max itself included).  Ascending, no duplicates."""
-    if boundary < 1 or sparse_step < 1 or n_max < 1 or after < 1 or after > boundary:
+    """Token counts to measure (see moe_curve_sample_counts in include/moe.h)."""
+    lib = load_library()
+    n = C.c_int32()
+    st = lib.moe_curve_sample_counts(boundary, dense_max, n_max, sparse_step, after, None, 0, C.byref(n))
+    if st != 0:
         raise ValueError("boundary, sparse_step, n_max must be positive and 1 <= after <= boundary")
-    dense_end = min(dense_max, n_max) // boundary * boundary
-    counts = {1}
-    for m in range(1, dense_end // boundary + 1):
-        counts.add(m * boundary)
-        if m * boundary + after <= n_max:
-            counts.add(m * boundary + after)
-    n = dense_end + sparse_step
-    while n < n_max:
-        counts.add(n)
-        n += sparse_step
-    counts.add(n_max)
-    return sorted(counts)
+    out = np.zeros(n.value, dtype=np.int32)
+    st = lib.moe_curve_sample_counts(boundary, dense_max, n_max, sparse_step, after, out.ctypes.data, n.value,
+                                     C.byref(n))
+    if st != 0:
+        raise MoEError(st, "moe_curve_sample_counts")
+    return out.tolist()
 
 
 @dataclass
@@ -44,24 +38,28 @@ class LatencyCurve:
     counts: Sequence[int]     # ascending sampled token counts
     ms: Sequence[float]       # measured latency at each of them
 
+    def _arrays(self):
+        return (np.ascontiguousarray(self.counts, dtype=np.int32), np.ascontiguousarray(self.ms, dtype=np.float64))
+
     def at(self, n: int) -> float:
-        """Latency at n tokens: the straight line between the neighbouring samples (the first
-        sample's value below it, the last one's above it, 0 for n <= 0)."""
-        if n <= 0:
-            return 0.0
-        j = bisect.bisect_left(self.counts, n)
-        if j >= len(self.counts):
-            return float(self.ms[-1])
-        if self.counts[j] == n or j == 0:
-            return float(self.ms[j])
-        lo, hi = self.counts[j - 1], self.counts[j]
-        t = (n - lo) / (hi - lo)
-        return float(self.ms[j - 1] + t * (self.ms[j] - self.ms[j - 1]))
+        """Latency at n tokens (moe_curve_eval)."""
+        c, m = self._arrays()
+        tok = np.array([n], dtype=np.int32)
+        out = np.zeros(1, dtype=np.float64)
+        st = load_library().moe_curve_eval(c.ctypes.data, m.ctypes.data, len(c), tok.ctypes.data, 1, out.ctypes.data)
+        if st != 0:
+            raise MoEError(st, "moe_curve_eval")
+        return float(out[0])
 
     def profiling_cost_ms(self, iters: int) -> float:
         """Kernel time spent taking the samples."""
         return float(sum(self.ms)) * iters
 
     def full_sweep_cost_ms(self, iters: int) -> float:
-        """Kernel time a sweep of every token count 1..max(counts) would take, from the rebuilt curve."""
-        return float(sum(self.at(n) for n in range(1, self.counts[-1] + 1))) * iters
+        """Kernel time a sweep of every token count 1..max(counts) would take (moe_curve_sum)."""
+        c, m = self._arrays()
+        out = C.c_double()
+        st = load_library().moe_curve_sum(c.ctypes.data, m.ctypes.data, len(c), 1, int(c[-1]), C.byref(out))
+        if st != 0:
+            raise MoEError(st, "moe_curve_sum")
+        return out.value * iters

@@ -1,27 +1,15 @@
-"""Helpers shared by the GPU parity tests (numpy bf16 bits <-> torch tensors, comparisons)."""
+"""Comparison helpers of the GPU parity tests.  Moving numpy buffers to the device and back is the
+package's job (paper_2605_19945_amd.tensors); the names are re-exported here for the tests."""
 import numpy as np
+
+from paper_2605_19945_amd.tensors import to_dev_bf16, to_dev, bits_of, f64_of_bf16  # noqa: F401
 
 NEAR_TIE = 1e-3      # logit gap below which two implementations may pick different experts
 OUT_TOL = 2e-2       # layer-output bound: bf16 operands, fp32 accumulation, bf16 H / Y / out
-
-
-def to_dev_bf16(bits):
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
-
-
-def to_dev(a):
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
-
-
-def bits_of(t):
-    import torch
-    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-
-
-def f64_of_bf16(t):
-    return (bits_of(t).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+# Regression gate against the oracle evaluated with H rounded to bf16 as the GPU stores it: what is left
+# is the rounding of Y and out (2^-9 relative each, independent) and fp32 summation order, i.e. an
+# expected per-row error of about sqrt(2) * 2^-9 / sqrt(3) = 1.6e-3 and a worst row well below 8e-3.
+TIGHT_TOL = 8e-3
 
 
 def check_routing(orc, logits, k, gpu_idx, gpu_w, gpu_counts):
@@ -56,13 +44,28 @@ def check_routing(orc, logits, k, gpu_idx, gpu_w, gpu_counts):
     return int((~clear).sum())
 
 
+def elementwise_violations(got, ref, tol=OUT_TOL):
+    """Number of elements with |got - ref| > tol * |ref| + tol * rms(ref) (reported next to the two gated
+    norms; a pure element-wise relative error is undefined at outputs near zero)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    return int((np.abs(got - ref) > tol * np.abs(ref) + tol * rms).sum())
+
+
 def check_output(got, ref, tol=OUT_TOL, what="out"):
-    """(i) per-row relative L2 error and (ii) max abs error over max |ref| both within tol."""
+    """(i) per-row relative L2 error and (ii) max abs error over max |ref| both within tol; elements off by
+    more than tol * |ref| + tol * rms(ref) -- six standard deviations of the expected rounding error -- may
+    number at most one in a million (none at all below a million elements)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape
     if ref.size == 0:
         return 0.0, 0.0
+    bad = elementwise_violations(got, ref, tol)
+    assert bad <= ref.size // 1000000, f"{what}: {bad} of {ref.size} elements off by more than {tol}*|ref| + {tol}*rms(ref)"
     nrm = np.linalg.norm(ref, axis=1)
     err = np.linalg.norm(got - ref, axis=1)
     live = nrm > 0

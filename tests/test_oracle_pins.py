@@ -333,6 +333,86 @@ def test_round_h_switch_only_moves_result_slightly():
     assert 0 < rel.max() < 2.0 ** -8
 
 
+def test_round_to_bf16_exact_values():
+    """The diagnostic rounding of the intermediate: nearest bf16, ties to the even mantissa.  Values chosen
+    so that truncation, round-half-up and round-half-away each fail at least one line."""
+    cases = [
+        (1.0 + 2.0 ** -8, 1.0),                       # exact tie between 1.0 and 1.0078125: even is 1.0
+        (1.0 + 3 * 2.0 ** -8, 1.015625),              # tie between 1.0078125 and 1.015625: even is 1.015625
+        (1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0078125),    # just above a tie: up
+        (1.0 + 2.0 ** -8 - 2.0 ** -20, 1.0),          # just below a tie: down
+        (-(1.0 + 2.0 ** -8), -1.0),                   # ties are symmetric in sign
+        (-(1.0 + 3 * 2.0 ** -8), -1.015625),
+        (1.0 + 2.0 ** -7 - 2.0 ** -12, 1.0078125),    # truncation would give 1.0
+        (3.0, 3.0), (0.0, 0.0), (-0.375, -0.375),     # representable values are unchanged
+        (2.0 ** -20 * (1.0 + 2.0 ** -8), 2.0 ** -20), # the tie rule does not depend on the exponent
+    ]
+    a = np.array([c[0] for c in cases], dtype=np.float64)
+    assert orc.round_to_bf16(a).tolist() == [c[1] for c in cases]
+    # every result is a bf16 value: the low 16 bits of its fp32 pattern are zero
+    r = orc.round_to_bf16(np.random.default_rng(1).standard_normal(1000))
+    assert (r.astype(np.float32).view(np.uint32) & 0xFFFF == 0).all()
+    assert np.abs(r - orc.round_to_bf16(r)).max() == 0
+
+
+def test_round_h_rounds_exactly_the_intermediate():
+    """expert_ffn(round_h_bf16=True) == W2 applied to the rounded silu(g) * u, with h rebuilt here by scalar
+    loops and rounded through the generator's (separately pinned) bf16 conversion."""
+    W1, W3, W2 = wl.expert_weights(31, 1, 8, 6, 0.5)
+    x = wl.gaussian_bf16_bits(31, 1, (3, 8), 1.0)
+    X = orc.widen_bf16(x)
+    got = orc.expert_ffn(X, W1[0], W3[0], W2[0], round_h_bf16=True)
+    w1, w3, w2 = orc.widen_bf16(W1[0]), orc.widen_bf16(W3[0]), orc.widen_bf16(W2[0])
+    for r in range(3):
+        h = []
+        for c in range(6):
+            g = sum(float(X[r, i]) * float(w1[i, c]) for i in range(8))
+            u = sum(float(X[r, i]) * float(w3[i, c]) for i in range(8))
+            h.append(g / (1.0 + math.exp(-g)) * u)
+        hb = orc.widen_bf16(wl.bf16_bits_from_f32(np.array(h, dtype=np.float32)))
+        for c in range(8):
+            want = sum(float(hb[j]) * float(w2[j, c]) for j in range(6))
+            assert abs(got[r, c] - want) <= 1e-12 * max(1.0, abs(want))
+
+
+def test_layer_forward_under_a_given_routing():
+    """The idx= / w= branch (the GPU tests evaluate the oracle under the GPU's own routing)."""
+    inp = wl.custom("t", 40, 32, 48, 8, 2, seed=29, wg_std=0.3, bias_std=0.4)
+    s = inp.shape
+    base = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k)
+    # (i) its own routing handed back in: identical result
+    same = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k, idx=base["idx"])
+    assert (same["out"] == base["out"]).all() and (same["w"] == base["w"]).all()
+    # (ii) the two slots exchanged: the gate weights follow their experts, the output is the same sum
+    swapped = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k, idx=base["idx"][:, ::-1].copy())
+    assert np.allclose(swapped["w"], base["w"][:, ::-1], rtol=1e-6, atol=0)
+    assert np.allclose(swapped["out"], base["out"], rtol=1e-6, atol=1e-12)
+    assert (swapped["counts"] == base["counts"]).all()
+    # (iii) slot 1 of a few tokens replaced by another expert: the row is the hand combination of that
+    # token's expert_ffn rows under the softmax of the two selected logits
+    idx = base["idx"].copy()
+    X = orc.widen_bf16(inp.x)
+    changed = [0, 7, 23]
+    for t in changed:
+        idx[t, 1] = next(e for e in range(s.E) if e not in base["idx"][t])
+    forced = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k, idx=idx)
+    for t in changed:
+        e0, e1 = int(idx[t, 0]), int(idx[t, 1])
+        l0, l1 = float(base["logits"][t, e0]), float(base["logits"][t, e1])
+        w1 = math.exp(l1 - l0) / (1.0 + math.exp(l1 - l0))
+        want = (1.0 - w1) * orc.expert_ffn(X[t:t + 1], inp.W1[e0], inp.W3[e0], inp.W2[e0])[0] \
+            + w1 * orc.expert_ffn(X[t:t + 1], inp.W1[e1], inp.W3[e1], inp.W2[e1])[0]
+        assert np.allclose(forced["out"][t], want, rtol=1e-6, atol=1e-12)
+    untouched = [t for t in range(s.T) if t not in changed]
+    assert (forced["out"][untouched] == base["out"][untouched]).all()
+    # (iv) gate weights handed in as well are used as they are
+    w = np.full_like(base["w"], 0.5)
+    half = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k, idx=base["idx"], w=w)
+    off, row_of, tok_of = orc.permutation(base["idx"], s.E)
+    Y = orc.grouped_ffn(orc.gather_rows(inp.x, tok_of), off, inp.W1, inp.W3, inp.W2)
+    assert np.allclose(half["out"], 0.5 * (Y[row_of[:, 0]] + Y[row_of[:, 1]]), rtol=1e-12, atol=1e-15)
+
+
 # ------------------------------------------------------------------ workload recipes
 def test_workloads_are_seeded_and_shaped():
     a, b, c = wl.tiny(0), wl.tiny(0), wl.tiny(1)
