@@ -18,8 +18,11 @@
  *   - Shapes: T tokens, d model width, f expert width, E experts seen by the router, k experts
  *     per token, experts [e_lo, e_lo+E_local) resident on this GPU.  d and f must be multiples
  *     of 64; 1 <= k <= min(E, 16); E <= 256; 1 <= E_local <= E.
- *   - Errors are return codes.  Arguments are validated on the host before any launch; a call
- *     that returns an error has launched nothing.  T == 0 is MOE_OK and a no-op.
+ *   - Errors are return codes.  Arguments are validated on the host before any launch: a call that
+ *     returns MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED_SHAPE or MOE_ERR_WORKSPACE_TOO_SMALL has launched
+ *     nothing.  MOE_ERR_DEVICE reports a HIP call that failed part-way; in a call of several stages
+ *     (moe_permute, moe_grouped_ffn, moe_layer_forward) the stages enqueued before it still run, and the
+ *     outputs are then undefined.  T == 0 is MOE_OK and a no-op.
  *   - Calls on one moe_ctx must not overlap in time (they share its workspace).
  *   - The calls that take a stream only launch kernels on it (no memsets, no allocation, no host
  *     synchronisation), so they may be recorded under stream capture and replayed as a HIP graph; the
@@ -98,7 +101,7 @@ moe_status moe_pack_weights(moe_ctx* ctx, const void* W1, const void* W3, const 
 
 /* ---- the hot path ---------------------------------------------------------------------------- */
 
-/* Router (paper Sec. 2.1 "a router selects a subset of experts for each token"; Sec. 3.3.1):
+/* Router (paper Sec. 2.1: per-token choice of the k experts; Sec. 3.3.1: its output is the trace):
  *   logit[t,e] = sum_i x[t,i] * Wg[i,e] (+ bias[e]);  topk_idx[t,0..k) = the k largest, slot 0
  *   the largest, equal logits resolved to the lower expert index;  topk_w[t,j] = softmax over
  *   the k selected logits;  counts[e] = number of (t, j) with topk_idx[t,j] == e, over all E.
@@ -107,7 +110,7 @@ moe_status moe_pack_weights(moe_ctx* ctx, const void* W1, const void* W3, const 
 moe_status moe_route(moe_ctx* ctx, const void* x, const void* router_packed, const float* bias,
                      int32_t T, int32_t* topk_idx, float* topk_w, int32_t* counts, void* stream);
 
-/* Dispatch by expert (paper Sec. 2.1 "dispatches it to the GPU(s) hosting those experts"):
+/* Dispatch by expert (paper Sec. 2.1: each token goes to where its experts are hosted):
  *   offsets[e'] = number of assignments to resident experts before e_lo + e' (exclusive prefix
  *   sum, offsets[E_local] = number of local assignments);  the destination row of (t, j) with
  *   e = topk_idx[t,j] resident is row_of[t,j] = offsets[e-e_lo] + #{t' < t : t' selected e}
@@ -118,7 +121,7 @@ moe_status moe_route(moe_ctx* ctx, const void* x, const void* router_packed, con
 moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T, void* xp,
                        int32_t* offsets, int32_t* row_of, int32_t* tok_of, void* stream);
 
-/* Expert FFN over expert-contiguous rows (the paper's "isolated MoE expert kernel", Sec. 3.3.2):
+/* Expert FFN over expert-contiguous rows (the expert kernel the paper profiles in isolation, Sec. 3.3.2):
  *   for offsets[e'] <= r < offsets[e'+1]:
  *       y[r, :] = W2[e']^T ( silu(W1[e']^T xp[r]) * (W3[e']^T xp[r]) )
  *   bf16 operands, fp32 accumulation; the intermediate [rows, f] is stored as bf16 in the

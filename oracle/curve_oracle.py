@@ -3,7 +3,7 @@ which token counts are sampled and how the token-vs-latency curve is rebuilt fro
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, never by the package.  Written with plain loops from
 the paper's description -- sample at the tile boundaries where latency jumps; at high token counts
-sample sparsely "at intervals of thousands of tokens" and rebuild the curve by linear interpolation
+sample sparsely (thousands of tokens apart) and rebuild the curve by linear interpolation
 -- independently of paper_2605_19945_amd/latency_curve.py (no shared code).
 
 Readings (the paper gives no formulas): the boundaries are the multiples of `boundary`; each is

@@ -1,4 +1,4 @@
-// Grouped expert GEMMs on the gfx950 matrix cores -- the paper's "isolated MoE expert kernel"
+// Grouped expert GEMMs on the gfx950 matrix cores -- the expert kernel the paper profiles in isolation
 // (Sec. 3.3.2), whose latency over token count is the staircase GEM samples at tile boundaries.
 //
 //   GEMM1 + SwiGLU:  H[r, c] = silu(sum_i X[r,i] W1[e][i,c]) * (sum_i X[r,i] W3[e][i,c])

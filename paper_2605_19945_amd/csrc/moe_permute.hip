@@ -1,7 +1,7 @@
 // Dispatch by expert: a stable counting sort of the (token, slot) assignments by resident expert.
 //
-// The paper says only that the router "dispatches [each token] to the GPU(s) hosting those
-// experts" (Sec. 2.1); inside one GPU that is the grouping of rows by expert computed here.
+// The paper says only that every token is sent to the GPUs that host its experts (Sec. 2.1);
+// inside one GPU that is the grouping of rows by expert computed here.
 // Order inside an expert is ascending token id, so the result is unique and reproducible.
 //
 // Three small kernels, no atomics on global memory, no waiting between workgroups (up to 512 tokens:

@@ -1,7 +1,7 @@
 // Router: logits = x * Wg (+ bias) on the matrix cores, top-k per token in one wavefront,
 // softmax over the selected logits, per-expert counts.
 //
-// The paper describes the router only as "selects a subset of experts for each token" (Sec. 2.1)
+// The paper describes the router in one sentence (it picks a few of the experts per token, Sec. 2.1)
 // and notes that its top-k output is where the expert-utilisation trace comes from (Sec. 3.3.1).
 //
 // Precision: x is bf16 (exact), Wg is fp32.  Wg is split once, at load time, into two bf16 terms

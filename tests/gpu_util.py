@@ -55,16 +55,17 @@ def elementwise_violations(got, ref, tol=OUT_TOL):
     return int((np.abs(got - ref) > tol * np.abs(ref) + tol * rms).sum())
 
 
-def check_output(got, ref, tol=OUT_TOL, what="out"):
+def check_output(got, ref, tol=OUT_TOL, what="out", elementwise=True):
     """(i) per-row relative L2 error and (ii) max abs error over max |ref| both within tol; elements off by
     more than tol * |ref| + tol * rms(ref) -- six standard deviations of the expected rounding error -- may
-    number at most one in a million (none at all below a million elements)."""
+    number at most one in a million (none at all below a million elements); elementwise=False leaves that
+    count out (the tighter regression gate bounds the two norms only)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape
     if ref.size == 0:
         return 0.0, 0.0
-    bad = elementwise_violations(got, ref, tol)
+    bad = elementwise_violations(got, ref, tol) if elementwise else 0
     assert bad <= ref.size // 1000000, f"{what}: {bad} of {ref.size} elements off by more than {tol}*|ref| + {tol}*rms(ref)"
     nrm = np.linalg.norm(ref, axis=1)
     err = np.linalg.norm(got - ref, axis=1)

@@ -94,7 +94,7 @@ def run_full_layer(moe, inp, n_random=192, max_near_frac=0.02):
     bad = gu.elementwise_violations(got, ref["out"])
     ref_h = orc.layer_forward(inp.x, inp.Wg, inp.bias, inp.W1, inp.W3, inp.W2, s.k, e_lo=s.e_lo, tokens=toks, idx=idx,
                               round_h_bf16=True)
-    row_rel_h, glob_h = gu.check_output(got, ref_h["out"], tol=gu.TIGHT_TOL, what=inp.name + " (H rounded)")
+    row_rel_h, glob_h = gu.check_output(got, ref_h["out"], tol=gu.TIGHT_TOL, what=inp.name + " (H rounded)", elementwise=False)
     n_e = np.diff(offsets)
     print(f"   near-ties {near}/{s.T}; {len(toks)} of {s.T} tokens checked: row_rel {row_rel:.2e}, glob {glob:.2e}, "
           f"element-wise violations {bad}/{got.size}; against the H-rounded oracle row_rel {row_rel_h:.2e}, glob {glob_h:.2e}; "
@@ -168,6 +168,6 @@ def test_ep_share_direct_groups(moe, N):
     ref = orc.grouped_ffn(xp, off, W1, W3, W2, rows=rows)
     row_rel, glob = gu.check_output(got[rows], ref, what=f"direct N={N}")
     ref_h = orc.grouped_ffn(xp, off, W1, W3, W2, rows=rows, round_h_bf16=True)
-    gu.check_output(got[rows], ref_h, tol=gu.TIGHT_TOL, what=f"direct N={N} (H rounded)")
+    gu.check_output(got[rows], ref_h, tol=gu.TIGHT_TOL, what=f"direct N={N} (H rounded)", elementwise=False)
     print(f"   {len(rows)} rows checked: row_rel {row_rel:.2e}, glob {glob:.2e}, tile rows {ctx.moe_tile_rows()}", flush=True)
     ctx.close()
