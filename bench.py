@@ -106,6 +106,56 @@ def time_layer_graph(moe, s, x, rp, bias, packed, out, steps, warmup):
     return dt / steps * 1e3
 
 
+def time_calls(fn, iters, warmup=3):
+    """Mean milliseconds of fn() over `iters` back-to-back calls (HIP events on the current stream)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def hbm_stages(moe, s, T, seed, iters=30):
+    """The three memory-bound stages on their own, each as `iters` back-to-back calls of its C-ABI entry point
+    on T tokens of the workload's shape (the router of the workload, Gaussian activations): algorithmic bytes
+    per call / mean time per call against the 8 TB/s HBM peak.  Algorithmic bytes: route 2*T*d + 8*T*k (+ the
+    packed router); permute, with the row copy, 2*(T + A)*d + 12*A; combine 2*(A + T)*d + 8*A, A = T*k local
+    assignments (all experts resident)."""
+    import torch
+    ctx = moe.MoEContext(T, s.d, 64, s.E, s.k)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.randn(T, s.d, device="cuda", generator=g).bfloat16()
+    Wg = torch.randn(s.d, s.E, device="cuda", generator=g) * 0.02
+    rp = ctx.moe_pack_router(Wg)
+    idx = torch.empty((T, s.k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, s.k), dtype=torch.float32, device="cuda")
+    counts = torch.empty(s.E, dtype=torch.int32, device="cuda")
+    A = T * s.k
+    out = {}
+    ms = time_calls(lambda: ctx.moe_route(x, rp, None, idx=idx, w=w, counts=counts), iters)
+    out["route"] = (2.0 * T * s.d + 8.0 * A + rp.numel() * 2, ms)
+    xp, offsets, row_of, tok_of = ctx.moe_permute(x, idx)
+    lib, cptr = ctx.lib, ctx._ctx
+    import ctypes as C
+    p = lambda t: C.c_void_p(t.data_ptr())
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ms = time_calls(lambda: lib.moe_permute(cptr, p(x), p(idx), T, p(xp), p(offsets), p(row_of), p(tok_of), st), iters)
+    out["permute"] = (2.0 * (T + A) * s.d + 12.0 * A, ms)
+    y = xp                                     # any [A, d] bf16 buffer serves as the experts' output
+    o = torch.empty((T, s.d), dtype=torch.bfloat16, device="cuda")
+    ms = time_calls(lambda: ctx.moe_combine(y, row_of, w, out=o), iters)
+    out["combine"] = (2.0 * (A + T) * s.d + 8.0 * A, ms)
+    ctx.close()
+    return {k: {"T": T, "bytes": b, "us": ms * 1e3, "GBps": b / ms / 1e6, "frac": b / ms / 1e6 / PEAK_HBM_GBS}
+            for k, (b, ms) in out.items()}
+
+
 def cpu_baseline(inp, sample_tokens):
     """The oracle as it stands, on a bounded sample of the workload's tokens, on the host cores."""
     import numpy as np
@@ -123,19 +173,53 @@ def cpu_baseline(inp, sample_tokens):
     dt = time.perf_counter() - t0
     local = ((r["idx"][tokens] >= s.e_lo) & (r["idx"][tokens] < s.e_lo + s.E_local)).sum()
     flops = 6.0 * local * s.d * s.f + 2.0 * s.T * s.d * s.E
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n} of {s.T} tokens ({int(local)} expert rows) of the same workload, fp64 numpy, "
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle", "cpu": model,
+            "sample": f"{n} of {s.T} tokens ({int(local)} expert rows) of the same workload, fp64 numpy + OpenBLAS, "
                       f"{dt:.1f} s wall"}
 
 
+def roofline_bound_ms(d, f, rows_per_expert, T_in=0):
+    """Lower bound of the expert FFN (plus, with T_in > 0, the layer's activation traffic) on one MI355X:
+    max(useful flop / bf16 MFMA peak, algorithmic bytes / HBM peak).  Bytes: packed weights of the experts that
+    have rows (6*d*f each), token rows in (2*d per row), the intermediate written and read (2 * 2*f per row),
+    expert outputs (2*d per row), and for a whole layer x read and out written (2 * 2*d per token)."""
+    rows = float(sum(rows_per_expert))
+    touched = sum(1 for n in rows_per_expert if n > 0)
+    flops = 6.0 * rows * d * f
+    bytes_ = 6.0 * d * f * touched + rows * (2 * d + 4 * f + 2 * d) + 4.0 * T_in * d
+    t_flop, t_byte = flops / (PEAK_BF16_TFLOPS * 1e12), bytes_ / (PEAK_HBM_GBS * 1e9)
+    return max(t_flop, t_byte) * 1e3, ("mfma" if t_flop >= t_byte else "hbm")
+
+
 def run_curve(moe, gu, weights_dev_packed, args):
-    """Latency vs per-GPU token load on the skewed Mixtral-shaped workload."""
+    """Latency vs per-GPU token load: the skewed Mixtral-shaped workload (config 3), the fine-grained layer
+    (config 4) and one GPU's expert-parallel share (config 5: already-routed groups and the decode-sized layer),
+    every row with its roofline bound and the fraction of it that was reached."""
     import torch
     import workloads as wl
-    ctx_shape = (wl.MIXTRAL_D, wl.MIXTRAL_F, wl.MIXTRAL_E, wl.MIXTRAL_K)
-    loads = [int(v) for v in args.curve_loads.split(",")]
     rows = []
-    ctx = moe.MoEContext(max(loads), *ctx_shape, flags=moe.FLAG_STAGE_EVENTS)
+
+    def record(name, tokens, ms, n_e, d, f, T_in, extra=None):
+        bound, kind = roofline_bound_ms(d, f, n_e, T_in)
+        flops = 6.0 * sum(n_e) * d * f
+        row = {"workload": name, "tokens": tokens, "ms": ms, "tflops": flops / ms / 1e9, "bound_ms": bound,
+               "bound": kind, "frac_of_bound": bound / ms, "rows_per_expert_max": int(max(n_e)), "rows": int(sum(n_e))}
+        row.update(extra or {})
+        rows.append(row)
+        log(f"curve {name} n={tokens}: {ms:.3f} ms  {row['tflops']:.1f} TFLOP/s  bound {bound:.3f} ms ({kind}) -> "
+            f"{row['frac_of_bound']:.1%} of the roofline")
+
+    # config 3
+    loads = [int(v) for v in args.curve_loads.split(",")]
+    ctx = moe.MoEContext(max(loads), wl.MIXTRAL_D, wl.MIXTRAL_F, wl.MIXTRAL_E, wl.MIXTRAL_K, flags=moe.FLAG_STAGE_EVENTS)
     for T in loads:
         inp = wl.mixtral_skewed(T, args.seed, weights=False)
         x = gu.to_dev_bf16(inp.x)
@@ -145,14 +229,49 @@ def run_curve(moe, gu, weights_dev_packed, args):
         counts = torch.empty(wl.MIXTRAL_E, dtype=torch.int32, device="cuda")
         ctx.moe_layer_forward(x, rp, bias, weights_dev_packed, out=out, counts_out=counts)
         ms, stages = time_layer(ctx, x, rp, bias, weights_dev_packed, out, args.curve_steps, 3)
-        flops = 6.0 * T * wl.MIXTRAL_K * wl.MIXTRAL_D * wl.MIXTRAL_F + 2.0 * T * wl.MIXTRAL_D * wl.MIXTRAL_E
-        rows.append({"tokens": T, "ms": ms, "tflops": flops / ms / 1e9, "tile_rows": ctx.moe_tile_rows(),
-                     "expert_counts": counts.cpu().tolist(), "stages_ms": stages})
-        log(f"curve T={T}: {ms:.3f} ms  {flops / ms / 1e9:.1f} TFLOP/s  counts={counts.cpu().tolist()}")
+        record("mixtral_skewed", T, ms, counts.cpu().tolist(), wl.MIXTRAL_D, wl.MIXTRAL_F, T,
+               {"tile_rows": ctx.moe_tile_rows(), "expert_counts": counts.cpu().tolist(), "stages_ms": stages})
     ctx.close()
+    del weights_dev_packed
+    torch.cuda.empty_cache()
+
+    def layer_point(name, inp):
+        s = inp.shape
+        c = moe.MoEContext(s.T, s.d, s.f, s.E, s.k, s.e_lo, s.E_local, flags=moe.FLAG_STAGE_EVENTS)
+        x = gu.to_dev_bf16(inp.x)
+        rp = c.moe_pack_router(gu.to_dev(inp.Wg))
+        bias = gu.to_dev(inp.bias) if inp.bias is not None else None
+        packed = c.moe_pack_weights(gu.to_dev_bf16(inp.W1), gu.to_dev_bf16(inp.W3), gu.to_dev_bf16(inp.W2))
+        out = torch.empty(s.T, s.d, dtype=torch.bfloat16, device="cuda")
+        counts = torch.empty(s.E, dtype=torch.int32, device="cuda")
+        c.moe_layer_forward(x, rp, bias, packed, out=out, counts_out=counts)
+        ms, stages = time_layer(c, x, rp, bias, packed, out, args.curve_steps, 3)
+        n_e = counts.cpu().tolist()[s.e_lo:s.e_lo + s.E_local]
+        record(name, s.T, ms, n_e, s.d, s.f, s.T, {"tile_rows": c.moe_tile_rows(), "stages_ms": stages})
+        c.close()
+        return packed
+
+    # config 4
+    layer_point("fine_grained", wl.fine_grained(8192, args.seed))
+    torch.cuda.empty_cache()
+    # config 5: the decode-sized layer, then the already-routed groups on the same packed weights
+    ep_w = wl.expert_weights(args.seed, wl.EP_ELOCAL, wl.EP_D, wl.EP_F)
+    packed = layer_point("ep_share_layer", wl.ep_share_layer(128, args.seed, weights=ep_w))
+    for N in (256, 1024, 4096, 16384):
+        xp_bits, off = wl.ep_share_groups(N, args.seed)
+        c = moe.MoEContext(N, wl.EP_D, wl.EP_F, wl.EP_ELOCAL, 1)
+        xp, offd = gu.to_dev_bf16(xp_bits), gu.to_dev(off)
+        y = torch.empty((N, wl.EP_D), dtype=torch.bfloat16, device="cuda")
+        ms = time_calls(lambda: c.moe_grouped_ffn(xp, offd, N, packed, y=y), args.curve_steps)
+        record("ep_share_groups", N, ms, np_diff(off), wl.EP_D, wl.EP_F, 0, {"tile_rows": c.moe_tile_rows()})
+        c.close()
     os.makedirs(os.path.join(ROOT, args.out_dir), exist_ok=True)
     with open(os.path.join(ROOT, args.out_dir, "latency_curve.json"), "w") as fh:
-        json.dump({"workload": "mixtral_skewed", "rows": rows}, fh, indent=1)
+        json.dump({"rows": rows}, fh, indent=1)
+
+
+def np_diff(off):
+    return [int(off[i + 1] - off[i]) for i in range(len(off) - 1)]
 
 
 def run_profile_curve(moe, s, packed, args):
@@ -254,8 +373,11 @@ def main():
     ap.add_argument("--out-dir", default=OUT_DIR_DEFAULT, help="folder (under the repo root) for the curve JSON files")
     ap.add_argument("--graph", action="store_true",
                     help="also time the layer call captured into a HIP graph and replayed")
-    ap.add_argument("--mfma-ceiling", action="store_true",
-                    help="also measure the bf16 MFMA rate the device sustains under an MFMA-only load")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the measurement of the bf16 MFMA rate the device sustains under an MFMA-only load")
+    ap.add_argument("--no-hbm-stages", action="store_true",
+                    help="skip the separate measurement of the memory-bound stages (route, permute, combine)")
+    ap.add_argument("--hbm-stage-tokens", default="4096,65536")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference for HBM byte counters)")
     ap.add_argument("--profile-curve", action="store_true",
@@ -327,7 +449,9 @@ def main():
                    "stages_ms": stages},
         "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel<SwiGLU> (GEMM1)", "achieved": g1,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": g1 / PEAK_BF16_TFLOPS,
-                     "traffic": profiled_traffic(inp.name, "gemm1") if args.tile_class < 0 else None},
+                     "traffic": profiled_traffic(inp.name, "gemm1") if args.tile_class < 0 else None,
+                     "traffic_source": "committed rocprofv3 --pmc summary of this command (profiles/), not this run",
+                     "gemm2": {"achieved": g2, "frac": g2 / PEAK_BF16_TFLOPS}},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(inp, args.cpu_sample_tokens)
@@ -335,7 +459,16 @@ def main():
         gms = time_layer_graph(moe, s, x, rp, bias, packed, out, args.steps, args.warmup)
         log(f"graph replay {gms:.3f} ms/step ({100 * (gms / ms - 1):+.1f} % against the eager calls)")
         result["graph_replay_ms_per_step"] = gms
-    if args.mfma_ceiling:
+    if not args.no_hbm_stages:
+        # route / permute / combine against the HBM roofline, at the workload's token count and at a large one
+        stages_hbm = []
+        for T in [int(v) for v in args.hbm_stage_tokens.split(",")]:
+            r = hbm_stages(moe, s, T, args.seed)
+            stages_hbm.append(r)
+            log(f"memory-bound stages at T={T}: " + ", ".join(
+                f"{k} {v['us']:.1f} us {v['GBps']:.0f} GB/s ({v['frac']:.0%} of HBM peak)" for k, v in r.items()))
+        result["roofline"]["hbm_stages"] = stages_hbm
+    if not args.no_mfma_ceiling:
         # context for roofline.frac, not a replacement of the published peak it is computed against
         sustained = moe.moe_measure_mfma_rate(2500, 5)
         log(f"sustained MFMA-only rate: {sustained:.0f} TFLOP/s = {100 * sustained / PEAK_BF16_TFLOPS:.1f} % of the "

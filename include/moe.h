@@ -130,7 +130,10 @@ moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int
  * n_rows_cap: host upper bound on offsets[E_local], at most moe_rows_capacity(shape, T_max).  The launches
  * are sized from it (the per-expert counts stay on the device), so a tight bound is cheaper than a loose
  * one; at low loads (up to 192 rows per expert on average) the second GEMM runs as several reduction
- * ranges whose fp32 partial sums are added in a fixed order. */
+ * ranges whose fp32 partial sums are added in a fixed order.  The bound is checked on the device: if
+ * offsets[E_local] exceeds n_rows_cap the call computes nothing (no row of y is written) and sets the flag
+ * moe_ffn_refused_flag points to; the host cannot see that without reading the flag, the return code stays
+ * MOE_OK. */
 moe_status moe_grouped_ffn(moe_ctx* ctx, const void* xp, const int32_t* offsets,
                            int32_t n_rows_cap, const void* packed, void* y, void* stream);
 
@@ -241,6 +244,11 @@ moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
  * `launches` >= 1 launches of iters_per_wave * 64 MFMAs per wavefront on `stream`, times them with events and waits for them.
  * tflops: host pointer.  Errors: MOE_ERR_INVALID_ARG, MOE_ERR_DEVICE. */
 moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops /* host */, void* stream);
+
+/* Device pointer (into the workspace) to an int32 that the most recent moe_grouped_ffn / moe_layer_forward /
+ * moe_profile_ffn call on this context set to 1 if it refused its offsets (offsets[E_local] above the host's
+ * row bound; nothing was computed) and to 0 otherwise. */
+moe_status moe_ffn_refused_flag(moe_ctx* ctx, const int32_t** flag);
 
 /* Device pointers into the workspace holding the intermediates of the most recent
  * moe_layer_forward: topk_idx [T,k], topk_w [T,k], offsets [E_local+1], row_of [T,k]. */

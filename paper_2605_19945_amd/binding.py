@@ -65,6 +65,7 @@ _SIGNATURES = {
     "moe_trace_mean_utilisation": (C.c_int, [_VP, _I32, _I32, _VP]),
     "moe_trace_correlation": (C.c_int, [_VP, _I32, _I32, _VP]),
     "moe_measure_mfma_rate": (C.c_int, [_I32, _I32, C.POINTER(C.c_float), _VP]),
+    "moe_ffn_refused_flag": (C.c_int, [_VP, C.POINTER(_VP)]),
     "moe_tile_rows": (_I32, [_VP]),
     "moe_set_tile_class": (C.c_int, [_VP, _I32]),
     "moe_layer_intermediates": (C.c_int, [_VP, C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP), C.POINTER(_VP)]),
@@ -234,6 +235,15 @@ class MoEContext:
         self._check(self.lib.moe_profile_ffn(self._ctx, _ptr(xp), _ptr(packed), _ptr(y), arr, len(counts), warmup,
                                              iters, ms, _stream()), "moe_profile_ffn")
         return [float(v) for v in ms]
+
+    def moe_ffn_refused(self):
+        """True if the most recent expert-FFN call on this context refused its offsets (blocks until it is done)."""
+        import torch
+        p = C.c_void_p()
+        self._check(self.lib.moe_ffn_refused_flag(self._ctx, C.byref(p)), "moe_ffn_refused_flag")
+        off = p.value - self.workspace.data_ptr()
+        torch.cuda.synchronize()
+        return bool(self.workspace[off:off + 4].view(torch.int32).item())
 
     def moe_tile_rows(self):
         return int(self.lib.moe_tile_rows(self._ctx))

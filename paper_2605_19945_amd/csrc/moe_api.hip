@@ -30,7 +30,7 @@ bool shape_ok(const moe_shape* s) {
 }
 
 struct Layout {
-    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, table_r, logits, route_ws, H, Y, part, total;
+    size_t idx, w, counts, offsets, row_of, tok_of, blockhist, table1, table2, table_r, logits, route_ws, refused, H, Y, part, total;
     int table1_cap, table2_cap;
     int64_t rows_cap;
 };
@@ -69,6 +69,7 @@ Layout make_layout(const moe_shape* s) {
         L.table_r = L.logits = 0;
     }
     L.route_ws = take((size_t)MOE_ROUTE_WS_INTS * 4);
+    L.refused = take(4);
     L.H = take((size_t)L.rows_cap * moe_ld_pad(s->f) * 2);
     L.Y = take((size_t)L.rows_cap * s->d * 2);
     L.part = take(moe_part_bytes(L.rows_cap, s->d));
@@ -90,6 +91,8 @@ inline moe_status note_hip(hipError_t e, const char* what) {
 inline moe_status from_hip(hipError_t e) { return note_hip(e, "kernel launch"); }
 
 }  // namespace
+
+void moe_note_error(const char* text) { snprintf(g_last_error, sizeof(g_last_error), "%s", text); }
 
 extern "C" {
 
@@ -169,6 +172,7 @@ moe_status moe_create(moe_ctx** out, const moe_shape* s, void* workspace, size_t
     c->table2 = (TileDesc*)(c->ws + L.table2);
     c->table_r = (TileDesc*)(c->ws + L.table_r);
     c->route_ws = (int32_t*)(c->ws + L.route_ws);
+    c->refused = (int32_t*)(c->ws + L.refused);
     c->logits = (float*)(c->ws + L.logits);
     c->H = (uint16_t*)(c->ws + L.H);
     c->Y = (uint16_t*)(c->ws + L.Y);
@@ -312,7 +316,7 @@ static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t*
     const uint16_t* w2f = packed + (size_t)s.E_local * 2 * s.f * s.d;
     // offsets[E_local] = the rows actually present
     const int nsplit = gemm_pick_split2(p, n_rows_cap, s.E_local, s.d, s.f, c->part_bytes);
-    hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, nsplit, st);
+    hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, nsplit, n_rows_cap, c->refused, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM1], st);
     e = launch_gemm1(p, X, s.d, row_map, w13f, s.d, s.f, c->H, c->table1, st);
@@ -437,6 +441,12 @@ moe_status moe_stage_times(moe_ctx* c, float* ms) {
             sum[i] += t;
         }
     for (int i = 0; i < MOE_NUM_STAGES; ++i) ms[i] = (float)(sum[i] / n);
+    return MOE_OK;
+}
+
+moe_status moe_ffn_refused_flag(moe_ctx* c, const int32_t** flag) {
+    if (c == nullptr || flag == nullptr) return MOE_ERR_INVALID_ARG;
+    *flag = c->refused;
     return MOE_OK;
 }
 

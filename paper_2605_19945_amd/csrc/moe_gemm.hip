@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
                                                        int bm, int bn, int nt1, int grid1,
                                                        TileDesc* __restrict__ t1, int nt2, int grid2,
                                                        TileDesc* __restrict__ t2, int host_rows, int nsplit1,
-                                                       int nsplit2) {
+                                                       int nsplit2, int rows_cap, int32_t* __restrict__ refused_out) {
     __shared__ int32_t s_off[257];
     __shared__ int32_t s_mte[256];     // row tiles of expert e
     __shared__ int32_t s_pre[257];     // pieces per weight-row tile of the experts before e; [E_local] = total
@@ -198,11 +198,15 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
             if (8 * longest <= grid) break;  // uniform
         }
 
+        // Offsets beyond the bound the launches and the buffers were sized for: nothing is scheduled (every
+        // entry stays empty, so no kernel touches a row) and the refusal is recorded for the caller.
+        const bool refused = host_rows < 0 && s_off[E_local] > rows_cap;
+        if (which == 0 && refused_out != nullptr && blockIdx.x == 0 && tid == 0) *refused_out = refused ? 1 : 0;
         for (int b = blockIdx.x * 256 + tid; b < grid; b += gridDim.x * 256) {
             const int x = b & 7, j = b >> 3;
             TileDesc td;
             td.expert = 0; td.row0 = 0; td.rows = 0; td.n0 = 0;
-            if (j < s_len[x][E_local]) {
+            if (!refused && j < s_len[x][E_local]) {
                 // the expert e with s_len[x][e] <= j < s_len[x][e + 1]
                 int lo = 0, hi = E_local;
                 while (hi - lo > 1) {
@@ -296,13 +300,13 @@ hipError_t gemm_init_attributes() {
 }
 
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1, TileDesc* t2,
-                           int nsplit2, hipStream_t st) {
+                           int nsplit2, int64_t rows_cap, int32_t* refused, hipStream_t st) {
     int g = p.grid1 > p.grid2 ? p.grid1 : p.grid2;
     int blocks = (g + 1023) / 1024;
     if (blocks < 1) blocks = 1;
     if (blocks > 64) blocks = 64;
     hipLaunchKernelGGL(schedule_kernel, dim3(blocks), dim3(256), 0, st, offsets, E_local, p.bm, p.bn, p.nt1,
-                       p.grid1, t1, p.nt2, p.grid2, t2, -1, 1, nsplit2);
+                       p.grid1, t1, p.nt2, p.grid2, t2, -1, 1, nsplit2, (int)rows_cap, refused);
     return hipGetLastError();
 }
 
@@ -354,8 +358,10 @@ int gemm_pick_split2(const GemmPlan& p, int64_t n_rows, int E_local, int d, int 
 // Y[r, c] = bf16(sum over the slabs of part[s][r][c]) for the rows r < *n_rows_dev
 __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, int nsplit,
                                                             size_t slab_elems, const int32_t* __restrict__ n_rows_dev,
-                                                            int d, uint16_t* __restrict__ Y) {
-    const size_t n = (size_t)*n_rows_dev * d / 4;  // quads of columns
+                                                            int n_rows_cap, int d, uint16_t* __restrict__ Y) {
+    const int rows = *n_rows_dev;
+    if (rows > n_rows_cap) return;  // refused by the scheduler: nothing was computed
+    const size_t n = (size_t)rows * d / 4;  // quads of columns
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
         f32x4_t acc = *(const f32x4_t*)(part + 4 * i);
         for (int s = 1; s < nsplit; ++s) {
@@ -382,7 +388,7 @@ hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2
     size_t blocks = (slab_elems / 4 + 255) / 256;
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)part, nsplit,
-                       slab_elems, n_rows_dev, d, Y);
+                       slab_elems, n_rows_dev, (int)n_rows, d, Y);
     return hipGetLastError();
 }
 
@@ -434,7 +440,8 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
     if (capture != hipStreamCaptureStatusNone) *table_T = -2;
     if (*table_T != T) {
         hipLaunchKernelGGL(schedule_kernel, dim3((grid + 1023) / 1024), dim3(256), 0, st, (const int32_t*)nullptr, 1,
-                           kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T, pk.nsplit, 1);
+                           kClassRows[c], GEMM_BN, nt, grid, table, 0, 0, (TileDesc*)nullptr, T, pk.nsplit, 1, T,
+                           (int32_t*)nullptr);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
         if (*table_T != -2) *table_T = T;

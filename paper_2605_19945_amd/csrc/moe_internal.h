@@ -51,6 +51,7 @@ struct moe_ctx {
     int table_r_T;       // token count table_r was built for; -1: none yet; -2: rebuild at every call
     float* logits;       // [T_max, router cols] fp32 (E >= MOE_ROUTER_GEMM_MIN_E)
     int32_t* route_ws;   // [MOE_ROUTE_WS_INTS] resident router: ticket (zero between launches) + partial counts
+    int32_t* refused;    // [1] 1 if the most recent work list was refused: offsets[E_local] exceeded the host's row bound
     uint16_t* H;         // [rows_cap, f] bf16
     uint16_t* Y;         // [rows_cap, d] bf16
     float* part;         // fp32 partial sums of a reduction split of GEMM2: [nsplit][n_rows, d]
@@ -91,6 +92,9 @@ static inline int moe_router_rows(int E) {  // packed router rows: multiple of 1
     return p * 16;
 }
 
+// Records the text moe_last_device_error() returns on this thread.
+void moe_note_error(const char* text);
+
 // ---- launchers (each validates nothing; the C-ABI layer has done that) -------------------------
 hipError_t launch_pack_router(const float* Wg, int d, int E, uint16_t* rp, hipStream_t st);
 hipError_t launch_pack_experts(const uint16_t* W1, const uint16_t* W3, const uint16_t* W2, int E_local,
@@ -115,7 +119,7 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
 // Slabs of partial router logits ([T, cols] fp32 each) the workspace holds for T tokens
 static inline int moe_router_split_cap(int T) { return T <= 8192 ? 8 : T <= 16384 ? 4 : T <= 32768 ? 2 : 1; }
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,
-                           TileDesc* t2, int nsplit2, hipStream_t st);
+                           TileDesc* t2, int nsplit2, int64_t rows_cap, int32_t* refused, hipStream_t st);
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table,
                         hipStream_t st);

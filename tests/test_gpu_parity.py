@@ -278,6 +278,27 @@ def test_grouped_ffn_all_rows_in_one_expert_and_rows_cap_larger_than_used(moe):
     ctx.close()
 
 
+def test_grouped_ffn_refuses_offsets_beyond_the_row_bound(moe):
+    """offsets[E_local] above n_rows_cap: the launches and the buffers are sized for n_rows_cap, so the device-side
+    scheduler refuses the work list: no row of y is written, the flag is set; the next proper call clears it."""
+    import torch
+    E_local, d, f, cap = 4, 128, 2048, 600          # f = 2048 and few rows: the split-reduction path as well
+    W1, W3, W2 = wl.expert_weights(9, E_local, d, f, 0.08)
+    xp = wl.gaussian_bf16_bits(9, 9, (cap, d), 1.0)
+    ctx = moe.MoEContext(cap, d, f, E_local, 1)
+    packed = ctx.moe_pack_weights(gu.to_dev_bf16(W1), gu.to_dev_bf16(W3), gu.to_dev_bf16(W2))
+    off = np.array([0, 100, 250, 380, 520], dtype=np.int32)
+    for bound in (300, 96):                          # both below offsets[E_local] = 520
+        y = torch.full((cap, d), 7.0, dtype=torch.bfloat16, device="cuda")
+        ctx.moe_grouped_ffn(gu.to_dev_bf16(xp), gu.to_dev(off), bound, packed, y=y)
+        assert ctx.moe_ffn_refused()
+        assert (y == 7.0).all(), "a refused call must not write"
+    y = ctx.moe_grouped_ffn(gu.to_dev_bf16(xp), gu.to_dev(off), 520, packed)
+    assert not ctx.moe_ffn_refused()
+    gu.check_output(gu.f64_of_bf16(y)[:520], orc.grouped_ffn(xp[:520], off, W1, W3, W2))
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------ combine
 def test_combine_parity(moe):
     import torch
