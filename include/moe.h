@@ -65,7 +65,8 @@ enum { MOE_STAGE_ROUTE = 0, MOE_STAGE_PERMUTE = 1, MOE_STAGE_GEMM1 = 2, MOE_STAG
 
 const char* moe_status_string(moe_status s);
 
-/* Text of the most recent failing HIP call behind a MOE_ERR_DEVICE on this thread ("" if none).
+/* Text of the most recent failing HIP call behind a MOE_ERR_DEVICE on this thread, or of a size limit that
+ * a call without a context exceeded ("" if none).
  * The pointer stays valid; the text changes with the next device error. */
 const char* moe_last_device_error(void);
 
@@ -120,6 +121,21 @@ moe_status moe_route(moe_ctx* ctx, const void* x, const void* router_packed, con
  * tok_of [rows_capacity]. */
 moe_status moe_permute(moe_ctx* ctx, const void* x, const int32_t* topk_idx, int32_t T, void* xp,
                        int32_t* offsets, int32_t* row_of, int32_t* tok_of, void* stream);
+
+/* moe_permute for callers that can neither allocate device memory nor bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  No context: the shape comes as
+ * arguments (d is only used for the row copy), the outputs are those of moe_permute, bit for bit.  The call
+ * allocates nothing and frees nothing; its only scratch, the per-256-token-block expert histograms, is a
+ * static device array of 1 MiB that every GPU the library runs on holds until the process ends.  Limit:
+ * ceil(T / 256) * E_local <= 262144 entries (e.g. T = 2^20 with up to 64 resident experts, T = 262144 with
+ * 256), otherwise MOE_ERR_WORKSPACE_TOO_SMALL with the sizes in moe_last_device_error(); T <= 2^20.  The array
+ * keeps the previous call's contents (every entry a call reads it has written itself first), and calls that
+ * overlap in time on one GPU share it and race: run them on one stream, or otherwise one after the other.
+ * The first call on a device looks up the array's device address (no allocation, but do it outside a
+ * stream capture). */
+moe_status moe_permute_noalloc(const void* x, const int32_t* topk_idx, int32_t T, int32_t d, int32_t E,
+                               int32_t k, int32_t e_lo, int32_t E_local, void* xp, int32_t* offsets,
+                               int32_t* row_of, int32_t* tok_of, void* stream);
 
 /* Expert FFN over expert-contiguous rows (the expert kernel the paper profiles in isolation, Sec. 3.3.2):
  *   for offsets[e'] <= r < offsets[e'+1]:

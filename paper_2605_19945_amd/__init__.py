@@ -14,4 +14,5 @@ from .binding import (  # noqa: F401
     moe_gem_score,
     moe_gem_place,
     moe_measure_mfma_rate,
+    moe_permute_noalloc,
 )

@@ -23,7 +23,7 @@ class MoEError(RuntimeError):
         self.status = status
         lib = load_library()
         msg = lib.moe_status_string(status).decode()
-        if status == 4:
+        if status in (3, 4) and lib.moe_last_device_error():
             msg += ": " + lib.moe_last_device_error().decode()
         super().__init__(f"{what}: {_STATUS.get(status, status)} ({msg})")
 
@@ -51,6 +51,7 @@ _SIGNATURES = {
     "moe_pack_weights": (C.c_int, [_VP, _VP, _VP, _VP, _VP, _VP]),
     "moe_route": (C.c_int, [_VP, _VP, _VP, _VP, _I32, _VP, _VP, _VP, _VP]),
     "moe_permute": (C.c_int, [_VP, _VP, _VP, _I32, _VP, _VP, _VP, _VP, _VP]),
+    "moe_permute_noalloc": (C.c_int, [_VP, _VP, _I32, _I32, _I32, _I32, _I32, _I32, _VP, _VP, _VP, _VP, _VP]),
     "moe_grouped_ffn": (C.c_int, [_VP, _VP, _VP, _I32, _VP, _VP, _VP]),
     "moe_combine": (C.c_int, [_VP, _VP, _VP, _VP, _I32, _VP, _VP]),
     "moe_layer_forward": (C.c_int, [_VP, _VP, _VP, _VP, _VP, _I32, _VP, _VP, _VP]),
@@ -265,6 +266,30 @@ class MoEContext:
         A = T * self.k
         return (view(p[0], A, torch.int32).view(T, self.k), view(p[1], A, torch.float32).view(T, self.k),
                 view(p[2], self.E_local + 1, torch.int32), view(p[3], A, torch.int32).view(T, self.k))
+
+
+def moe_permute_noalloc(x, topk_idx, E, e_lo=0, E_local=-1, xp=None, offsets=None, row_of=None, tok_of=None):
+    """moe_permute without a context (scratch in the library's static device array).  The outputs are
+    allocated here unless the caller passes them; the library call itself allocates nothing."""
+    import torch
+    lib = load_library()
+    T, k = topk_idx.shape
+    E_local = E if E_local < 0 else E_local
+    d = x.shape[1] if x is not None else 0
+    cap = max(1, T * min(k, E_local))
+    dev = topk_idx.device
+    if xp is None and x is not None:
+        xp = torch.empty((cap, d), dtype=torch.bfloat16, device=dev)
+    offsets = torch.empty(E_local + 1, dtype=torch.int32, device=dev) if offsets is None else offsets
+    row_of = torch.empty((T, k), dtype=torch.int32, device=dev) if row_of is None else row_of
+    tok_of = torch.empty(cap, dtype=torch.int32, device=dev) if tok_of is None else tok_of
+    if T == 0:
+        offsets.zero_()
+    st = lib.moe_permute_noalloc(_ptr(x), _ptr(topk_idx), T, d, E, k, e_lo, E_local, _ptr(xp), _ptr(offsets),
+                                 _ptr(row_of), _ptr(tok_of), _stream())
+    if st != 0:
+        raise MoEError(st, "moe_permute_noalloc")
+    return xp, offsets, row_of, tok_of
 
 
 # ---- host-side mapping search (no context, no GPU) ------------------------------------------------

@@ -11,6 +11,10 @@
 //   3. per block: rank of every assignment among the block's earlier tokens, from per-wavefront
 //      64-bit membership masks in LDS -> row_of, tok_of.
 // The row copy itself (xp[row_of[t, j]] = x[t]) is a separate streaming kernel.
+#include <stdio.h>
+
+#include <mutex>
+
 #include "moe_internal.h"
 
 constexpr int PB = 256;  // tokens per block (one token per thread)
@@ -281,4 +285,71 @@ hipError_t launch_combine(const uint16_t* y, const int32_t* row_of, const float*
     hipLaunchKernelGGL(combine_kernel, dim3(T * blocks_per_row), dim3(threads), 0, st, (const uint4*)y, row_of,
                        w, T, k, chunks, (uint4*)out);
     return hipGetLastError();
+}
+
+// ---- dispatch without a context or a workspace ------------------------------------------------------
+// For callers that can neither allocate device memory nor hand over a workspace.  The only scratch the
+// three-kernel path needs, the per-block expert histograms, lives in a static device array: every device
+// the library runs on holds its own copy, at its own address, until the process ends.  The array's name is
+// only a host-side handle; its device address is looked up once per device and the kernels get that address
+// as an ordinary argument.  Every entry the scan and rank kernels read is first written by the histogram
+// kernel of the same call, so nothing has to be cleared between calls; calls that overlap in time on one
+// device share the array and race.
+constexpr int PERMUTE_STATIC_INTS = 262144;  // 1 MiB: ceil(T / 256) * E_local block-histogram entries
+static __device__ __align__(256) int32_t g_permute_static_scratch[PERMUTE_STATIC_INTS];
+
+constexpr int PERMUTE_MAX_DEVICES = 64;
+static int32_t* g_permute_static_ptr[PERMUTE_MAX_DEVICES];  // device address of the array, per device
+static std::mutex g_permute_static_mutex;
+
+// Device address of the current device's copy of the static scratch array (looked up on first use).
+static hipError_t permute_static_scratch(int32_t** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= PERMUTE_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_permute_static_mutex);
+    if (g_permute_static_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_permute_static_scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_permute_static_ptr[dev] = (int32_t*)p;
+    }
+    *out = g_permute_static_ptr[dev];
+    return hipSuccess;
+}
+
+extern "C" moe_status moe_permute_noalloc(const void* x, const int32_t* topk_idx, int32_t T, int32_t d, int32_t E,
+                                          int32_t k, int32_t e_lo, int32_t E_local, void* xp, int32_t* offsets,
+                                          int32_t* row_of, int32_t* tok_of, void* stream) {
+    auto misaligned = [](const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; };
+    if (T < 0 || T > (1 << 20) || E < 1 || E > 256 || k < 1 || k > 16 || k > E || e_lo < 0 || E_local < 1 ||
+        (int64_t)e_lo + E_local > E)
+        return MOE_ERR_INVALID_ARG;
+    if (topk_idx == nullptr || offsets == nullptr || row_of == nullptr || tok_of == nullptr) return MOE_ERR_INVALID_ARG;
+    if (misaligned(topk_idx, 4) || misaligned(offsets, 4) || misaligned(row_of, 4) || misaligned(tok_of, 4))
+        return MOE_ERR_INVALID_ARG;
+    if (xp != nullptr && (x == nullptr || d < 8 || d % 8 != 0 || misaligned(x, 16) || misaligned(xp, 16)))
+        return MOE_ERR_INVALID_ARG;
+    const int64_t nblk = ((int64_t)T + PB - 1) / PB;
+    if (nblk * E_local > PERMUTE_STATIC_INTS) {
+        char msg[200];
+        snprintf(msg, sizeof(msg),
+                 "moe_permute_noalloc: T = %d tokens and %d resident experts need %lld scratch entries, the static "
+                 "array holds %d", T, E_local, (long long)(nblk * E_local), PERMUTE_STATIC_INTS);
+        moe_note_error(msg);
+        return MOE_ERR_WORKSPACE_TOO_SMALL;
+    }
+    if (T == 0) return MOE_OK;
+    hipStream_t st = (hipStream_t)stream;
+    int32_t* scratch = nullptr;
+    hipError_t e = permute_static_scratch(&scratch);
+    if (e == hipSuccess) e = launch_permute(topk_idx, T, k, e_lo, E_local, scratch, offsets, row_of, tok_of, st);
+    if (e == hipSuccess && xp != nullptr) e = launch_gather((const uint16_t*)x, row_of, T, k, d, (uint16_t*)xp, st);
+    if (e != hipSuccess) {
+        moe_note_error(hipGetErrorString(e));
+        return MOE_ERR_DEVICE;
+    }
+    return MOE_OK;
 }
