@@ -248,9 +248,11 @@ moe_status moe_gem_place(const int32_t* trace, int32_t S, int32_t E, int32_t G, 
                          const float* noise /* [K][E] */, int32_t K, int32_t* mapping_out /* [E] */,
                          double* score_out, int32_t* swaps_out /* or NULL */);
 
-/* Tuning hook: force the token-tile class of the expert GEMMs (0: row tiles of up to 128 rows, the
- * low-load class; 1: up to 288 rows, the main class; higher values select alternative kernels kept
- * for tuning runs; -1: choose from the expected rows per expert, the default). */
+/* Tuning hook: force the token-tile class of the expert GEMMs (1: row tiles of up to 288 rows, the main
+ * class; 5: the class of decode-sized loads -- two wavefronts per workgroup, 128 weight rows and up to 64
+ * token rows per work item, four workgroups to a compute unit; 0, 2, 3, 4: alternative kernels with row tiles
+ * of up to 128, 64, 32, 256 rows kept for tuning runs; -1: choose from the expected rows per expert, the
+ * default: class 0 below 12 rows per expert, class 5 up to 24, class 1 above). */
 moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
 
 /* Measurement aid for roofline reports: the bf16 matrix-core rate this device SUSTAINS under a load of

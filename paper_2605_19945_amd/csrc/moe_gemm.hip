@@ -254,8 +254,10 @@ __global__ __launch_bounds__(256) void schedule_kernel(const int32_t* __restrict
 // moe_gemm_kernel.h: 0 = 128-row tiles (very low loads), 1 = 288-row tiles (main), 2 = 64, 3 = 32,
 // 4 = 256.
 // ------------------------------------------------------------------------------------------------
-static const int kClassRows[GEMM_NUM_CLASSES] = {128, 288, 64, 32, 256};
-constexpr int GEMM_BN = 256;
+static const int kClassRows[GEMM_NUM_CLASSES] = {128, 288, 64, 32, 256, 64};
+static const int kClassBn[GEMM_NUM_CLASSES] = {256, 256, 256, 256, 256, 128};   // packed weight rows per work item
+static const int kClassPerCu[GEMM_NUM_CLASSES] = {1, 1, 2, 3, 1, 4};            // workgroups that share a compute unit
+constexpr int GEMM_BN = 256;  // of the classes the router-logit GEMM uses
 
 #define DECL(name)                                                                                         \
     hipError_t gemm_set_attr_##name();                                                                     \
@@ -268,17 +270,20 @@ DECL(swiglu) DECL(plain) DECL(pairsum) DECL(partial)
 int gemm_class_rows(int cls) { return kClassRows[cls]; }
 
 int gemm_pick_class(double rows_per_expert) {
-    // Measured on the expert-parallel share (32 experts, Zipf loads): the tall class wins from
-    // about 32 rows per expert upwards; at 8 rows per expert the 128-row class streams the weights
-    // about 1 % faster.
-    return rows_per_expert < 12.0 ? GEMM_LOW : GEMM_MAIN;
+    // Measured (Mixtral shape and the expert-parallel share, layer time): below 12 rows per expert the
+    // 128-row class is the fastest of the weight-streaming launches (4 to 8 rows per expert: 0.225 / 0.238 /
+    // 0.235 ms for the classes 0 / 5 / 1 on the expert-parallel share); from 12 to 24 rows per expert the
+    // decode class (16 and 24 rows per expert on the Mixtral shape: 0.562 against 0.572 and 0.566 against
+    // 0.580 ms); above that the tall class (it wins from about 32 rows per expert upwards).
+    if (rows_per_expert < 12.0) return GEMM_LOW;
+    return rows_per_expert <= 24.0 ? GEMM_DECODE : GEMM_MAIN;
 }
 
 GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f) {
     GemmPlan p;
     p.cls = cls;
     p.bm = kClassRows[cls];
-    p.bn = GEMM_BN;
+    p.bn = kClassBn[cls];
     int64_t extra = n_rows_cap < E_local ? n_rows_cap : E_local;
     // Row tiles at the tallest cap number at most rows / bm + one per loaded expert; a quarter more lets the
     // scheduler pick lower caps (it only considers caps whose tiles fit the list).
@@ -335,6 +340,19 @@ int gemm_pick_split2(const GemmPlan& p, int64_t n_rows, int E_local, int d, int 
     const double items = (double)tiles * p.nt2;
     const double w_bytes = (double)e_loaded * d * f * 2;
     const int KT = f / 64;
+    if (p.cls == GEMM_DECODE) {
+        // decode class: the launch only streams weights; split until every compute unit holds as many workgroups
+        // as fit on it (each keeps two K steps of its weight panel in flight)
+        const double want = (double)SCHED_CU * kClassPerCu[GEMM_DECODE];
+        int pick = 1;
+        for (int s = 1; s <= 8; ++s) {
+            if (KT % s != 0 || KT / s < 16) continue;
+            if ((double)s * n_rows * d * 4 > (double)part_bytes) continue;
+            pick = s;
+            if (items * s >= want) break;
+        }
+        return pick;
+    }
     auto cost = [&](int s) {
         const double rounds = (double)(((int64_t)(items * s) + SCHED_CU - 1) / SCHED_CU);
         double c = rounds * (1.0 / s + 0.06);

@@ -267,16 +267,17 @@ static __device__ inline void wait_vmcnt_rt(int n) {
 // length): workgroup (x, y) reduces over elements [y*K, (y+1)*K) of the K_total = gridDim.y * K long
 // reduction dimension and writes its partial result c_split_bytes behind that of split y-1; the
 // consumer adds the partial results in a fixed order.
-template <int BM, int NSX, int EPI>
-__global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
+template <int BM, int NSX, int EPI, int NW>
+__global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
                                                       const int32_t* __restrict__ row_map,
                                                       const uint16_t* __restrict__ Wf, int Np, int K,
                                                       uint16_t* __restrict__ C, int ldc,
                                                       const TileDesc* __restrict__ table,
                                                       size_t c_split_bytes) {
-    constexpr int BN = 256, BK = 64, NW = 4, TN = BN / NW, FN = TN / 32, FM = BM / 32;
+    constexpr int BN = 64 * NW, BK = 64, TN = BN / NW, FN = TN / 32, FM = BM / 32;
     constexpr int CH = BK / 8;   // 16-byte chunks per staged token row
     constexpr int RPL = 64 / CH; // rows covered by one wave-level load
+    constexpr int XP = 32 / (NW * RPL);  // wave-level token loads of one wavefront per 32-row block
     constexpr int KK = BK / 16;  // MFMA sub-steps per K step
     constexpr int DX = NSX - 1;  // token prefetch distance (K steps)
     constexpr int WPF = 2;       // weight prefetch distance (K steps); WPF + 1 register buffers
@@ -285,7 +286,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
     constexpr int BLK = 32 * CH * 16;         // bytes between consecutive 32-row blocks in a stage
     static_assert(FN == 2 && KK == 4, "wave tile");
     static_assert(BM % 32 == 0 && FM >= 1 && FM <= 9, "row tile");
-    static_assert(NSX >= 3 && (2 * FM + WL) <= 32, "pipeline depth");
+    static_assert(NW == 4 || NW == 2, "wavefronts per workgroup");
+    static_assert(NSX >= 3 && (2 * FM * XP + WL) <= 48, "pipeline depth");
 
     extern __shared__ u32x4_t lds[];  // [NSX][STAGE]
 
@@ -302,11 +304,11 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
     X += (size_t)blockIdx.y * K;
     C = (uint16_t*)((char*)C + (size_t)blockIdx.y * c_split_bytes);
 
-    // token sources: pass p of a wavefront brings rows 32*p + 8*wave .. +8 of the tile (one pass per
+    // token sources: pass p of a wavefront brings rows 8*(NW*p + wave) .. +8 of the tile (XP passes per
     // 32-row block), 32-bit byte offsets from the wave-uniform base X + kt*BK
-    uint32_t xo[FM];
+    uint32_t xo[FM * XP];
 #pragma unroll
-    for (int p = 0; p < FM; ++p) {
+    for (int p = 0; p < FM * XP; ++p) {
         const int r = (p * NW + wave) * RPL + lrow;
         const int rr = r < td.rows ? r : td.rows - 1;  // clamp: rows past the end are never stored
         int grow = td.row0 + rr;
@@ -341,7 +343,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
     auto main_loop = [&](auto fmv_c) {
         constexpr int FMV = decltype(fmv_c)::value;  // valid 32-row blocks (compile time)
         constexpr int NM = FMV * FN;                 // MFMAs per sub-step
-        constexpr int NL = WL + FMV;                 // loads per lane per K step
+        constexpr int XV = FMV * XP;                 // token loads per lane per K step
+        constexpr int NL = WL + XV;                  // loads per lane per K step
 
         bf16x8_t wr[WPF + 1][KK][FN];
         bf16x8_t xf[2][FMV];
@@ -369,7 +372,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
         };
         // prologue: weights of stages 0, 1 and tokens of stages 0 .. DX-1, oldest needs first
         static_for<WL>([&](auto j) { load_w_one(0, std::integral_constant<int, 0>{}, j); });
-        static_for<FMV>([&](auto p) { issue_x_one(0, p); });
+        static_for<XV>([&](auto p) { issue_x_one(0, p); });
         int after0 = 0;  // loads issued after those of stage 0
         if (1 < KT) {
             static_for<WL>([&](auto j) { load_w_one(1, std::integral_constant<int, 1>{}, j); });
@@ -378,8 +381,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
 #pragma unroll
         for (int s = 1; s < DX; ++s)
             if (s < KT) {
-                static_for<FMV>([&](auto p) { issue_x_one(s, p); });
-                after0 += FMV;
+                static_for<XV>([&](auto p) { issue_x_one(s, p); });
+                after0 += XV;
             }
         wait_vmcnt_rt(after0);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -408,14 +411,14 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
                     // stage kt+1, and everything issued during this step), all wavefronts have issued
                     // and completed every LDS read of stage kt
                     if constexpr (STEADY) {
-                        wait_vmcnt<WL + 2 * FMV>();
+                        wait_vmcnt<WL + 2 * XV>();
                     } else {
-                        int pending = (more_w ? WL : 0) + (more_x ? FMV : 0);
+                        int pending = (more_w ? WL : 0) + (more_x ? XV : 0);
                         if (kt >= 1) {
-                            pending += kt - 1 + DX < KT ? FMV : 0;
+                            pending += kt - 1 + DX < KT ? XV : 0;
                         } else {
 #pragma unroll
-                            for (int s = 2; s < DX; ++s) pending += s < KT ? FMV : 0;  // issued by the prologue
+                            for (int s = 2; s < DX; ++s) pending += s < KT ? XV : 0;  // issued by the prologue
                         }
                         if (next) wait_vmcnt_rt(pending);
                     }
@@ -510,41 +513,50 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const uint16_t* __res
 
 
 // ---- per-epilogue instantiation units ----------------------------------------------------------
-// Classes 0 and 1 are the production token-tile classes (row tiles of up to 128 rows for very low
-// loads, up to 288 rows otherwise); higher ids are alternatives kept for tuning runs
-// (moe_set_tile_class).
+// Classes 0 and 1 are the production token-tile classes of ordinary loads (row tiles of up to 128 rows for
+// low loads, up to 288 rows otherwise), class 5 the one of decode-sized loads (see below); the other ids are
+// alternatives kept for tuning runs (moe_set_tile_class).
+// Class 5: two wavefronts per workgroup, 128 packed weight rows and up to 64 token rows per work item.  At a
+// few rows per expert the kernel only streams weights, and what bounds it is the number of bytes a compute
+// unit has in flight: a 4-wavefront workgroup with all its registers keeps 64 KB of weights under way and
+// occupies the compute unit alone; these workgroups need under 256 registers per lane and 33 KB of LDS, four
+// of them share a compute unit, together they keep 128 KB under way, and the weight panels are half as large,
+// so a launch has four times as many workgroups to spread over the device (Mixtral shape, 64 tokens: 1792
+// instead of 896 for 256 compute units).
 // A unit that defines MOE_GEMM_NO_TALL_TILE before including this file leaves out the 288-row class (its
 // launcher then rejects class 1): the router-logit GEMM never uses it, and with that unit's epilogue the
 // compiler copies the VGPR accumulators right behind their MFMAs (see mfma_pinned_vgpr).
-//   V(id, BM, NSX)
+//   V(id, BM, NSX, NW)
 #ifdef MOE_GEMM_NO_TALL_TILE
 #define FOR_EACH_VARIANT(V) \
-    V(0, 128, 4)            \
-    V(2, 64, 4)             \
-    V(3, 32, 4)             \
-    V(4, 256, 4)
+    V(0, 128, 4, 4)         \
+    V(2, 64, 4, 4)          \
+    V(3, 32, 4, 4)          \
+    V(4, 256, 4, 4)         \
+    V(5, 64, 4, 2)
 #else
 #define FOR_EACH_VARIANT(V) \
-    V(0, 128, 4)            \
-    V(1, 288, 4)            \
-    V(2, 64, 4)             \
-    V(3, 32, 4)             \
-    V(4, 256, 4)
+    V(0, 128, 4, 4)         \
+    V(1, 288, 4, 4)         \
+    V(2, 64, 4, 4)          \
+    V(3, 32, 4, 4)          \
+    V(4, 256, 4, 4)         \
+    V(5, 64, 4, 2)
 #endif
 
-template <int BM, int NSX, int EPI>
+template <int BM, int NSX, int EPI, int NW>
 struct Variant {
     static constexpr size_t smem = (size_t)NSX * BM * 64 * 2;
     static hipError_t set_attr() {
-        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, NSX, EPI>,
+        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, NSX, EPI, NW>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     // K is the reduction length of ONE split; nsplit = 1 for the expert GEMMs
     static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wf,
                              int Np, int K, uint16_t* C, int ldc, const TileDesc* table, int nsplit,
                              size_t c_split_bytes, hipStream_t st) {
-        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI>), dim3(grid, nsplit), dim3(256), smem, st, X, ldx,
-                           row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
+        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI, NW>), dim3(grid, nsplit), dim3(NW * 64), smem, st, X,
+                           ldx, row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
         return hipGetLastError();
     }
 };
@@ -563,16 +575,16 @@ struct Variant {
         switch (cls) { FOR_EACH_VARIANT(MOE_GEMM_CASE_##EPI) }                                                \
         return hipErrorInvalidValue;                                                                          \
     }
-#define MOE_GEMM_SET_ATTR(EPI, bm, ns)            \
-    err = Variant<bm, ns, EPI>::set_attr();       \
+#define MOE_GEMM_SET_ATTR(EPI, bm, ns, nw)        \
+    err = Variant<bm, ns, EPI, nw>::set_attr();   \
     if (err != hipSuccess) return err;
-#define MOE_GEMM_CASE(EPI, id, bm, ns) \
-    case id: return Variant<bm, ns, EPI>::launch(grid, X, ldx, row_map, Wf, Np, K, C, ldc, table, nsplit, c_split_bytes, st);
-#define MOE_GEMM_SET_ATTR_EPI_PLAIN(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PLAIN, bm, ns)
-#define MOE_GEMM_SET_ATTR_EPI_SWIGLU(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_SWIGLU, bm, ns)
-#define MOE_GEMM_SET_ATTR_EPI_PAIR_SUM_F32(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PAIR_SUM_F32, bm, ns)
-#define MOE_GEMM_SET_ATTR_EPI_PARTIAL_F32(id, bm, ns) MOE_GEMM_SET_ATTR(EPI_PARTIAL_F32, bm, ns)
-#define MOE_GEMM_CASE_EPI_PLAIN(id, bm, ns) MOE_GEMM_CASE(EPI_PLAIN, id, bm, ns)
-#define MOE_GEMM_CASE_EPI_SWIGLU(id, bm, ns) MOE_GEMM_CASE(EPI_SWIGLU, id, bm, ns)
-#define MOE_GEMM_CASE_EPI_PAIR_SUM_F32(id, bm, ns) MOE_GEMM_CASE(EPI_PAIR_SUM_F32, id, bm, ns)
-#define MOE_GEMM_CASE_EPI_PARTIAL_F32(id, bm, ns) MOE_GEMM_CASE(EPI_PARTIAL_F32, id, bm, ns)
+#define MOE_GEMM_CASE(EPI, id, bm, ns, nw) \
+    case id: return Variant<bm, ns, EPI, nw>::launch(grid, X, ldx, row_map, Wf, Np, K, C, ldc, table, nsplit, c_split_bytes, st);
+#define MOE_GEMM_SET_ATTR_EPI_PLAIN(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_PLAIN, bm, ns, nw)
+#define MOE_GEMM_SET_ATTR_EPI_SWIGLU(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_SWIGLU, bm, ns, nw)
+#define MOE_GEMM_SET_ATTR_EPI_PAIR_SUM_F32(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_PAIR_SUM_F32, bm, ns, nw)
+#define MOE_GEMM_SET_ATTR_EPI_PARTIAL_F32(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_PARTIAL_F32, bm, ns, nw)
+#define MOE_GEMM_CASE_EPI_PLAIN(id, bm, ns, nw) MOE_GEMM_CASE(EPI_PLAIN, id, bm, ns, nw)
+#define MOE_GEMM_CASE_EPI_SWIGLU(id, bm, ns, nw) MOE_GEMM_CASE(EPI_SWIGLU, id, bm, ns, nw)
+#define MOE_GEMM_CASE_EPI_PAIR_SUM_F32(id, bm, ns, nw) MOE_GEMM_CASE(EPI_PAIR_SUM_F32, id, bm, ns, nw)
+#define MOE_GEMM_CASE_EPI_PARTIAL_F32(id, bm, ns, nw) MOE_GEMM_CASE(EPI_PARTIAL_F32, id, bm, ns, nw)

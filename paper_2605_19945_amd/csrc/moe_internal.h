@@ -20,7 +20,7 @@ struct TileDesc {
 };
 
 // Token-tile classes of the grouped GEMM.
-enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_NUM_CLASSES = 5 };
+enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_DECODE = 5, GEMM_NUM_CLASSES = 6 };
 
 struct GemmPlan {
     int cls;         // GemmClass

@@ -198,6 +198,11 @@ FFN_CASES = [
     ("gemm2_two_splits", 4, 128, 2048, 100, -1),
     ("gemm2_four_splits", 8, 256, 4096, 300, 1),
     ("gemm2_splits_low_class", 3, 320, 2048, 20, 0),
+    # decode class: two wavefronts per workgroup, 128 weight rows and up to 64 token rows per work item
+    ("decode_class", 6, 128, 256, 90, 5),
+    ("decode_class_ragged_widths", 3, 320, 448, 70, 5),      # d, f not multiples of the 128-row weight tile
+    ("decode_class_many_row_tiles", 2, 192, 384, 700, 5),    # far more rows than the class is meant for
+    ("decode_class_split_reduction", 8, 256, 4096, 100, 5),
     ("auto", 8, 128, 256, 640, -1),
 ]
 
@@ -241,7 +246,7 @@ def test_grouped_ffn_random_shapes(moe):
         total = int(rng.choice([1, 7, 33, 150, 700, 2500, 6000]))
         while total * d * f > 1.2e9:
             total //= 2
-        cls = int(rng.choice([-1, -1, 0, 1, 4]))
+        cls = int(rng.choice([-1, -1, 0, 1, 4, 5]))
         off = ragged_offsets(rng, E_local, total, empty_frac=float(rng.choice([0.0, 0.3, 0.7])))
         print(f"random ffn case {case}: E_local={E_local} d={d} f={f} rows={total} class={cls} "
               f"max rows/expert={int(np.diff(off).max())}", flush=True)
@@ -267,7 +272,7 @@ def test_grouped_ffn_all_rows_in_one_expert_and_rows_cap_larger_than_used(moe):
     xp = wl.gaussian_bf16_bits(8, 9, (cap, d), 1.0)
     ctx = moe.MoEContext(cap, d, f, E_local, 1)
     packed = ctx.moe_pack_weights(gu.to_dev_bf16(W1), gu.to_dev_bf16(W3), gu.to_dev_bf16(W2))
-    for cls in range(5):
+    for cls in range(6):
         ctx.moe_set_tile_class(cls)
         y = torch.full((cap, d), 7.0, dtype=torch.bfloat16, device="cuda")
         ctx.moe_grouped_ffn(gu.to_dev_bf16(xp), gu.to_dev(off), cap, packed, y=y)
@@ -365,7 +370,7 @@ def test_layer_parity(moe, case):
     ctx.close()
 
 
-@pytest.mark.parametrize("cls", list(range(5)))
+@pytest.mark.parametrize("cls", list(range(6)))
 def test_layer_parity_every_tile_class(moe, cls):
     print(f"layer tile class {cls}", flush=True)
     inp = wl.custom("cls", 700, 128, 256, 8, 2, seed=cls, wg_std=0.08, w_std=0.06)
