@@ -305,19 +305,28 @@ moe_status moe_permute(moe_ctx* c, const void* x, const int32_t* topk_idx, int32
     return from_hip(e);
 }
 
+// The two expert GEMMs.  plan == nullptr: the work lists are built here from offsets (one more launch);
+// otherwise they have been built for *plan with nsplit reduction ranges of the second GEMM.  Y == nullptr
+// with nsplit > 1 leaves the second GEMM's partial sums in c->part for the caller.
 static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t* row_map,
                           const int32_t* offsets, int64_t n_rows_cap, const uint16_t* packed, uint16_t* Y,
-                          hipStream_t st, hipEvent_t* events) {
+                          hipStream_t st, hipEvent_t* events, const GemmPlan* plan = nullptr, int nsplit = 1) {
     const moe_shape& s = c->s;
-    GemmPlan p = gemm_make_plan(cls, n_rows_cap, s.E_local, s.d, s.f);
-    if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    GemmPlan p;
+    hipError_t e;
+    if (plan != nullptr) {
+        p = *plan;
+    } else {
+        p = gemm_make_plan(cls, n_rows_cap, s.E_local, s.d, s.f);
+        if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
+        nsplit = gemm_pick_split2(p, n_rows_cap, s.E_local, s.d, s.f, c->part_bytes);
+        // offsets[E_local] = the rows actually present
+        e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, nsplit, n_rows_cap, c->refused, st);
+        if (e != hipSuccess) return MOE_ERR_DEVICE;
+    }
     c->last_cls = cls;
     const uint16_t* w13f = packed;
     const uint16_t* w2f = packed + (size_t)s.E_local * 2 * s.f * s.d;
-    // offsets[E_local] = the rows actually present
-    const int nsplit = gemm_pick_split2(p, n_rows_cap, s.E_local, s.d, s.f, c->part_bytes);
-    hipError_t e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, nsplit, n_rows_cap, c->refused, st);
-    if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (events) (void)hipEventRecord(events[MOE_STAGE_GEMM1], st);
     e = launch_gemm1(p, X, s.d, row_map, w13f, s.d, s.f, c->H, c->table1, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
@@ -405,20 +414,35 @@ moe_status moe_layer_forward(moe_ctx* c, const void* x, const void* rp, const fl
     hipEvent_t* ev = c->ev != nullptr ? c->ev[c->ev_count % MOE_EVENT_RING] : nullptr;
     int32_t* counts = counts_out != nullptr ? counts_out : c->counts;
 
+    // everything the host decides is decided before the first launch: tile class, work-list sizes, splits
+    const int64_t cap = moe_rows_capacity(&s, T);
+    const int cls = c->forced_cls >= 0 ? c->forced_cls : gemm_pick_class((double)T * s.k / s.E);
+    const GemmPlan p = gemm_make_plan(cls, cap, s.E_local, s.d, s.f);
+    if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    const int nsplit = gemm_pick_split2(p, cap, s.E_local, s.d, s.f, c->part_bytes);
+    const SchedArgs sa = gemm_sched_args(p, s.E_local, c->table1, c->table2, nsplit, cap, c->refused);
+    // up to a few hundred tokens the dispatch is one workgroup that counts for itself
+    const bool plan_counts = dispatch_plan_counts_itself(T);
+
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_ROUTE], st);
     hipError_t e = launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, s.d, s.E, s.k, c->idx, c->w,
-                                counts, c->logits, logits_slabs(c, T), c->table_r, &c->table_r_T, c->route_ws, st);
+                                plan_counts ? nullptr : counts, c->logits, logits_slabs(c, T), c->table_r,
+                                &c->table_r_T, c->route_ws, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_PERMUTE], st);
-    e = launch_permute(c->idx, T, s.k, s.e_lo, s.E_local, c->blockhist, c->offsets, c->row_of, c->tok_of, st);
+    e = launch_dispatch_plan(c->idx, T, s.k, s.E, s.e_lo, c->blockhist, plan_counts ? counts_out : counts, c->offsets,
+                             c->row_of, c->tok_of, sa, gemm_sched_blocks(p), st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
-    // the row copy is folded into GEMM1: it reads x through tok_of
-    int cls = c->forced_cls >= 0 ? c->forced_cls : gemm_pick_class((double)T * s.k / s.E);
-    moe_status ms = run_ffn(c, cls, (const uint16_t*)x, c->tok_of, c->offsets, moe_rows_capacity(&s, T),
-                            (const uint16_t*)packed, c->Y, st, ev);
+    // the row copy is folded into GEMM1: it reads x through tok_of; the split second GEMM leaves fp32
+    // partial sums that the combine adds up itself
+    moe_status ms = run_ffn(c, cls, (const uint16_t*)x, c->tok_of, c->offsets, cap, (const uint16_t*)packed,
+                            nsplit > 1 ? nullptr : c->Y, st, ev, &p, nsplit);
     if (ms != MOE_OK) return ms;
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_COMBINE], st);
-    e = launch_combine(c->Y, c->row_of, c->w, T, s.k, s.d, (uint16_t*)out, st);
+    if (nsplit > 1)
+        e = launch_combine_split(c->part, nsplit, (size_t)cap * s.d, c->row_of, c->w, T, s.k, s.d, (uint16_t*)out, st);
+    else
+        e = launch_combine(c->Y, c->row_of, c->w, T, s.k, s.d, (uint16_t*)out, st);
     if (e != hipSuccess) return MOE_ERR_DEVICE;
     if (ev) {
         (void)hipEventRecord(ev[MOE_NUM_STAGES], st);

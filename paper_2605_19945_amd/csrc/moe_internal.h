@@ -19,6 +19,19 @@ struct TileDesc {
     int32_t n0;      // first packed weight row
 };
 
+// What a work-list build needs besides the per-expert rows.
+struct SchedArgs {
+    int E_local;
+    int bm, bn;            // tallest row tile, packed weight rows per work item
+    int nt1, grid1;        // weight-row tiles and work-list entries of the first GEMM
+    TileDesc* t1;
+    int nt2, grid2;        // of the second GEMM (grid2 = 0: none)
+    TileDesc* t2;
+    int nsplit1, nsplit2;  // reduction splits (workgroups per entry) of the two launches
+    int rows_cap;          // host bound on the total rows (-1: none); exceeded -> nothing is scheduled
+    int32_t* refused_out;  // where that refusal is recorded (or nullptr)
+};
+
 // Token-tile classes of the grouped GEMM.
 enum GemmClass { GEMM_LOW = 0, GEMM_MAIN = 1, GEMM_DECODE = 5, GEMM_NUM_CLASSES = 6 };
 
@@ -120,6 +133,20 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
 static inline int moe_router_split_cap(int T) { return T <= 8192 ? 8 : T <= 16384 ? 4 : T <= 32768 ? 2 : 1; }
 hipError_t launch_schedule(const GemmPlan& p, const int32_t* offsets, int E_local, TileDesc* t1,
                            TileDesc* t2, int nsplit2, int64_t rows_cap, int32_t* refused, hipStream_t st);
+// Arguments of a work-list build for plan p, and the workgroups worth spending on it
+SchedArgs gemm_sched_args(const GemmPlan& p, int E_local, TileDesc* t1, TileDesc* t2, int nsplit2, int64_t rows_cap,
+                          int32_t* refused);
+int gemm_sched_blocks(const GemmPlan& p);
+// Dispatch of the layer: offsets, row_of, tok_of and both work lists from idx (and the router's counts).
+// dispatch_plan_counts_itself(T): the launch counts the assignments itself (counts is an output, may be null,
+// and the router need not count); otherwise counts[E] is the router's and is read.
+bool dispatch_plan_counts_itself(int T);
+hipError_t launch_dispatch_plan(const int32_t* idx, int T, int k, int E, int e_lo, int32_t* blockhist, int32_t* counts,
+                                int32_t* offsets, int32_t* row_of, int32_t* tok_of, const SchedArgs& a, int sched_blocks,
+                                hipStream_t st);
+// moe_combine on rows that still lie as nsplit fp32 partial slabs (slab_elems floats apart) of the second GEMM
+hipError_t launch_combine_split(const float* part, int nsplit, size_t slab_elems, const int32_t* row_of, const float* w,
+                                int T, int k, int d, uint16_t* out, hipStream_t st);
 hipError_t launch_gemm1(const GemmPlan& p, const uint16_t* X, int ldx, const int32_t* row_map,
                         const uint16_t* W13f, int d, int f, uint16_t* H, const TileDesc* table,
                         hipStream_t st);

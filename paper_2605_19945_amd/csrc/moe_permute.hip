@@ -16,6 +16,7 @@
 #include <mutex>
 
 #include "moe_internal.h"
+#include "moe_schedule.h"
 
 constexpr int PB = 256;  // tokens per block (one token per thread)
 constexpr int PW = PB / 64;
@@ -107,10 +108,14 @@ __global__ __launch_bounds__(PB) void permute_rank_kernel(const int32_t* __restr
 // batches the three launches and the gaps between them cost more than the work (permute + work-list
 // stage at 64 tokens: 29 -> 17 us; from about four blocks on the three kernels are faster).
 constexpr int PF_BLOCKS = 2;
+// PLAN (plan_small_kernel of the layer): the same workgroup also counts the assignments of all E experts
+// (counts_out, may be null) and builds the work lists of the expert GEMMs from the offsets it has just formed.
+template <bool PLAN>
 __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __restrict__ idx, int T, int k, int e_lo,
                                                            int E_local, int32_t* __restrict__ offsets,
                                                            int32_t* __restrict__ row_of,
-                                                           int32_t* __restrict__ tok_of) {
+                                                           int32_t* __restrict__ tok_of, int E,
+                                                           int32_t* __restrict__ counts_out, SchedArgs a) {
     __shared__ int32_t hist[PF_BLOCKS * 256];         // [block][E_local] -> assignments to e in earlier blocks
     __shared__ unsigned long long masks[PW * 256];   // [wave][E_local]
     __shared__ int32_t wbase[PW * 256];
@@ -118,16 +123,20 @@ __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __rest
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nblk = (T + PB - 1) / PB;
     for (int o = tid; o < nblk * E_local; o += PB) hist[o] = 0;
+    if (PLAN && counts_out != nullptr) wbase[tid] = 0;  // (free until the ranks) assignments per expert, all E
     __syncthreads();
     for (int b = 0; b < nblk; ++b) {
         const int t = b * PB + tid;
         if (t < T)
             for (int j = 0; j < k; ++j) {
-                const int e = idx[(size_t)t * k + j] - e_lo;
+                const int eg = idx[(size_t)t * k + j];
+                if (PLAN && counts_out != nullptr) atomicAdd(&wbase[eg], 1);
+                const int e = eg - e_lo;
                 if (e >= 0 && e < E_local) atomicAdd(&hist[b * E_local + e], 1);
             }
     }
     __syncthreads();
+    if (PLAN && counts_out != nullptr && tid < E) counts_out[tid] = wbase[tid];
     int run = 0;
     if (tid < E_local)
         for (int b = 0; b < nblk; ++b) {
@@ -178,14 +187,116 @@ __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __rest
         }
         __syncthreads();  // masks and wbase are rewritten for the next block
     }
+    if constexpr (PLAN) {
+        // the exclusive prefix the scheduler wants: tot is the inclusive scan over the resident experts
+        int32_t* s_off = hist;  // (no longer read) [E_local + 1]
+        if (tid < E_local) s_off[tid + 1] = tot[tid];
+        if (tid == 0) s_off[0] = 0;
+        __syncthreads();
+        schedule_tables(a, s_off, 0, 1);
+    }
+}
+
+// ---- dispatch inside moe_layer_forward: permutation and GEMM work lists together -------------------------
+// The router has already counted the assignments per expert, and the work lists of the expert GEMMs depend on
+// nothing else; only the ranks need the per-block histograms.  So the layer runs
+//     plan_kernel:           blocks [0, nblk): block histograms (as permute_hist_kernel)
+//                            the other blocks: offsets from the router's counts, both work lists
+//     permute_rank2_kernel:  per block, the prefix over the earlier blocks' histograms (the scan of
+//                            permute_scan_kernel, redone by every block: nblk * E_local integers), then the ranks
+// two launches between the router and the first GEMM instead of four (histogram, scan, ranks, work lists), and
+// the work lists, the longest of them, are built next to the histograms instead of after the ranks.  Up to
+// PF_BLOCKS blocks of tokens everything happens in ONE workgroup (plan_small_kernel), which then also counts
+// the assignments itself, so that the router can skip its cross-workgroup count reduction.
+__global__ __launch_bounds__(PB) void plan_kernel(const int32_t* __restrict__ idx, int T, int k, int e_lo, int nblk,
+                                                  int32_t* __restrict__ blockhist,
+                                                  const int32_t* __restrict__ counts,
+                                                  int32_t* __restrict__ offsets, SchedArgs a) {
+    const int E_local = a.E_local;
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x < nblk) {
+        __shared__ int32_t hist[256];
+        hist[tid] = 0;
+        __syncthreads();
+        const int t = blockIdx.x * PB + tid;
+        if (t < T)
+            for (int j = 0; j < k; ++j) {
+                const int e = idx[(size_t)t * k + j] - e_lo;
+                if (e >= 0 && e < E_local) atomicAdd(&hist[e], 1);
+            }
+        __syncthreads();
+        if (tid < E_local) blockhist[(size_t)blockIdx.x * E_local + tid] = hist[tid];
+        return;
+    }
+    __shared__ int32_t s_off[257];
+    __shared__ int32_t s_scan[4];
+    const int rows = tid < E_local ? counts[e_lo + tid] : 0;
+    const int incl = block_scan_incl(rows, s_scan);
+    if (tid < E_local) s_off[tid + 1] = incl;
+    if (tid == 0) s_off[0] = 0;
+    __syncthreads();
+    const int part = blockIdx.x - nblk, parts = gridDim.x - nblk;
+    if (part == 0)
+        for (int i = tid; i <= E_local; i += PB) offsets[i] = s_off[i];
+    schedule_tables(a, s_off, part, parts);
+}
+
+__global__ __launch_bounds__(PB) void permute_rank2_kernel(const int32_t* __restrict__ idx, int T, int k, int e_lo,
+                                                           int E_local, const int32_t* __restrict__ blockhist,
+                                                           const int32_t* __restrict__ offsets,
+                                                           int32_t* __restrict__ row_of, int32_t* __restrict__ tok_of) {
+    extern __shared__ unsigned long long masks[];          // [PW][E_local] lanes of wave w that selected e
+    int32_t* wbase = (int32_t*)(masks + PW * E_local);     // [PW][E_local] rows of e in earlier waves
+    int32_t* before = wbase + PW * E_local;                // [E_local] assignments to e in earlier blocks
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int o = tid; o < PW * E_local; o += PB) masks[o] = 0ull;
+    for (int e = tid; e < E_local; e += PB) before[e] = 0;
+    __syncthreads();
+    // prefix over the earlier blocks: thread (g, e) adds the blocks g, g + G, ... and the G partial sums meet in LDS
+    int Ep = 1;
+    while (Ep < E_local) Ep <<= 1;
+    const int G = PB / Ep, e_mine = tid % Ep, g = tid / Ep;
+    if (e_mine < E_local) {
+        int sum = 0;
+        for (int b = g; b < (int)blockIdx.x; b += G) sum += blockhist[(size_t)b * E_local + e_mine];
+        if (sum != 0) atomicAdd(&before[e_mine], sum);
+    }
+    const int t = blockIdx.x * PB + tid;
+    if (t < T)
+        for (int j = 0; j < k; ++j) {
+            int e = idx[(size_t)t * k + j] - e_lo;
+            if (e >= 0 && e < E_local) atomicOr(&masks[wave * E_local + e], 1ull << lane);
+        }
+    __syncthreads();
+    for (int e = tid; e < E_local; e += PB) {
+        int run = offsets[e] + before[e];
+#pragma unroll
+        for (int ww = 0; ww < PW; ++ww) {
+            wbase[ww * E_local + e] = run;
+            run += __popcll(masks[ww * E_local + e]);
+        }
+    }
+    __syncthreads();
+    if (t < T) {
+        const unsigned long long below = (1ull << lane) - 1ull;
+        for (int j = 0; j < k; ++j) {
+            int e = idx[(size_t)t * k + j] - e_lo;
+            int r = -1;
+            if (e >= 0 && e < E_local) {
+                r = wbase[wave * E_local + e] + __popcll(masks[wave * E_local + e] & below);
+                tok_of[r] = t;
+            }
+            row_of[(size_t)t * k + j] = r;
+        }
+    }
 }
 
 hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_local, int32_t* blockhist,
                           int32_t* offsets, int32_t* row_of, int32_t* tok_of, hipStream_t st) {
     int nblk = (T + PB - 1) / PB;
     if (nblk <= PF_BLOCKS) {
-        hipLaunchKernelGGL(permute_fused_kernel, dim3(1), dim3(PB), 0, st, idx, T, k, e_lo, E_local, offsets, row_of,
-                           tok_of);
+        hipLaunchKernelGGL(permute_fused_kernel<false>, dim3(1), dim3(PB), 0, st, idx, T, k, e_lo, E_local, offsets,
+                           row_of, tok_of, 0, (int32_t*)nullptr, SchedArgs{});
         return hipGetLastError();
     }
     hipLaunchKernelGGL(permute_hist_kernel, dim3(nblk), dim3(PB), E_local * sizeof(int32_t), st, idx, T, k,
@@ -194,6 +305,27 @@ hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_loca
     size_t smem = (size_t)PW * E_local * (sizeof(unsigned long long) + sizeof(int32_t));
     hipLaunchKernelGGL(permute_rank_kernel, dim3(nblk), dim3(PB), smem, st, idx, T, k, e_lo, E_local,
                        blockhist, offsets, row_of, tok_of);
+    return hipGetLastError();
+}
+
+bool dispatch_plan_counts_itself(int T) { return (T + PB - 1) / PB <= PF_BLOCKS; }
+
+// Permutation plus work lists of the layer (see plan_kernel).  counts: the router's per-expert counts over all E
+// experts; with dispatch_plan_counts_itself(T) they are an OUTPUT here (or null), otherwise an input.
+hipError_t launch_dispatch_plan(const int32_t* idx, int T, int k, int E, int e_lo, int32_t* blockhist, int32_t* counts,
+                                int32_t* offsets, int32_t* row_of, int32_t* tok_of, const SchedArgs& a, int sched_blocks,
+                                hipStream_t st) {
+    const int nblk = (T + PB - 1) / PB, E_local = a.E_local;
+    if (nblk <= PF_BLOCKS) {
+        hipLaunchKernelGGL(permute_fused_kernel<true>, dim3(1), dim3(PB), 0, st, idx, T, k, e_lo, E_local, offsets,
+                           row_of, tok_of, E, counts, a);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(plan_kernel, dim3(nblk + sched_blocks), dim3(PB), 0, st, idx, T, k, e_lo, nblk, blockhist,
+                       (const int32_t*)counts, offsets, a);
+    const size_t smem = (size_t)PW * E_local * (sizeof(unsigned long long) + sizeof(int32_t)) + (size_t)E_local * 4;
+    hipLaunchKernelGGL(permute_rank2_kernel, dim3(nblk), dim3(PB), smem, st, idx, T, k, e_lo, E_local,
+                       (const int32_t*)blockhist, (const int32_t*)offsets, row_of, tok_of);
     return hipGetLastError();
 }
 
@@ -275,6 +407,53 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
     o.z = pack_bf16x2(acc[4], acc[5]);
     o.w = pack_bf16x2(acc[6], acc[7]);
     out[(size_t)t * chunks + c] = o;
+}
+
+// The same sum when the second GEMM ran as nsplit reduction ranges: the expert output row is first formed from
+// its partial sums (added in slab order, rounded to bf16 exactly as reduce_splits_kernel stores it), so the
+// result equals moe_combine on the reduced rows bit for bit and the reduced rows are never written.
+__global__ __launch_bounds__(256) void combine_split_kernel(const float* __restrict__ part, int nsplit,
+                                                            size_t slab_elems, const int32_t* __restrict__ row_of,
+                                                            const float* __restrict__ w, int T, int k, int chunks,
+                                                            uint4* __restrict__ out) {
+    const int chunks_per_block = blockDim.x;
+    const int blocks_per_row = (chunks + chunks_per_block - 1) / chunks_per_block;
+    const int t = blockIdx.x / blocks_per_row;
+    const int c = (blockIdx.x % blocks_per_row) * chunks_per_block + threadIdx.x;
+    if (t >= T || c >= chunks) return;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < k; ++j) {
+        const int r = row_of[(size_t)t * k + j];
+        if (r < 0) continue;
+        const float g = w[(size_t)t * k + j];
+        const float* src = part + ((size_t)r * chunks + c) * 8;
+        f32x4_t lo = *(const f32x4_t*)src, hi = *(const f32x4_t*)(src + 4);
+        for (int sp = 1; sp < nsplit; ++sp) {
+            const f32x4_t l2 = *(const f32x4_t*)(src + sp * slab_elems), h2 = *(const f32x4_t*)(src + sp * slab_elems + 4);
+            lo[0] += l2[0]; lo[1] += l2[1]; lo[2] += l2[2]; lo[3] += l2[3];
+            hi[0] += h2[0]; hi[1] += h2[1]; hi[2] += h2[2]; hi[3] += h2[3];
+        }
+        for (int q = 0; q < 4; ++q) {
+            acc[q] += g * (float)(__bf16)lo[q];
+            acc[4 + q] += g * (float)(__bf16)hi[q];
+        }
+    }
+    uint4 o;
+    o.x = pack_bf16x2(acc[0], acc[1]);
+    o.y = pack_bf16x2(acc[2], acc[3]);
+    o.z = pack_bf16x2(acc[4], acc[5]);
+    o.w = pack_bf16x2(acc[6], acc[7]);
+    out[(size_t)t * chunks + c] = o;
+}
+
+hipError_t launch_combine_split(const float* part, int nsplit, size_t slab_elems, const int32_t* row_of, const float* w,
+                                int T, int k, int d, uint16_t* out, hipStream_t st) {
+    int chunks = d / 8;
+    int threads = chunks >= 256 ? 256 : (chunks + 63) / 64 * 64;
+    int blocks_per_row = (chunks + threads - 1) / threads;
+    hipLaunchKernelGGL(combine_split_kernel, dim3(T * blocks_per_row), dim3(threads), 0, st, part, nsplit, slab_elems,
+                       row_of, w, T, k, chunks, (uint4*)out);
+    return hipGetLastError();
 }
 
 hipError_t launch_combine(const uint16_t* y, const int32_t* row_of, const float* w, int T, int k, int d,

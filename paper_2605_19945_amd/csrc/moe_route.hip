@@ -256,6 +256,7 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(const uint16_t* __restri
         }
     }
     __syncthreads();
+    if (counts == nullptr) return;  // the caller counts the assignments itself
     for (int e = tid; e < E; e += NW * 64)
         if (hist[e] != 0) atomicAdd(&counts[e], hist[e]);
 }
@@ -333,6 +334,7 @@ __global__ __launch_bounds__(RR_NW * 64) void route_resident_kernel(
 #pragma unroll
         for (int s = 0; s < RR_MAXS; ++s) xf[s] = xn[s];
     }
+    if (counts == nullptr) return;  // (kernel argument, uniform) the caller counts the assignments itself
     __syncthreads();
     // per-workgroup counts -> workspace; the last workgroup to arrive sums them.  Device-scope
     // atomics only (they are performed at the memory side, past the per-XCD L2s): the partial counts
@@ -393,7 +395,7 @@ __global__ __launch_bounds__(256) void topk_kernel(const float* __restrict__ log
         const size_t o = (size_t)t * k + lane;
         idx[o] = my_e;
         w[o] = gate;
-        atomicAdd(&sub_counts[(blockIdx.x % TOPK_SUB) * E + my_e], 1);
+        if (sub_counts != nullptr) atomicAdd(&sub_counts[(blockIdx.x % TOPK_SUB) * E + my_e], 1);
     }
 }
 
@@ -445,14 +447,14 @@ hipError_t launch_route(const uint16_t* x, const uint16_t* rp, const float* bias
         if (err != hipSuccess) return err;
         const int blocks = (T + 3) / 4;
         const int epl = (E + 63) / 64;
-        int32_t* sub = route_ws + MOE_ROUTE_WS_SUBCOUNTS;
+        int32_t* sub = counts != nullptr ? route_ws + MOE_ROUTE_WS_SUBCOUNTS : nullptr;
         if (epl <= 1) hipLaunchKernelGGL(topk_kernel<1>, dim3(blocks), dim3(256), 0, st, logits_ws, Ep, nsplit, bias, T, E, k, idx, w, sub);
         else if (epl == 2) hipLaunchKernelGGL(topk_kernel<2>, dim3(blocks), dim3(256), 0, st, logits_ws, Ep, nsplit, bias, T, E, k, idx, w, sub);
         else hipLaunchKernelGGL(topk_kernel<4>, dim3(blocks), dim3(256), 0, st, logits_ws, Ep, nsplit, bias, T, E, k, idx, w, sub);
-        hipLaunchKernelGGL(reduce_counts_kernel, dim3(1), dim3(256), 0, st, sub, E, counts);
+        if (counts != nullptr) hipLaunchKernelGGL(reduce_counts_kernel, dim3(1), dim3(256), 0, st, sub, E, counts);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(zero_i32_kernel, dim3((E + 255) / 256), dim3(256), 0, st, counts, E);
+    if (counts != nullptr) hipLaunchKernelGGL(zero_i32_kernel, dim3((E + 255) / 256), dim3(256), 0, st, counts, E);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     int nb = moe_router_rows(E) / 16;

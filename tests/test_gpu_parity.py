@@ -121,6 +121,33 @@ def test_route_zero_rows_and_bias_only(moe):
     ctx.close()
 
 
+@pytest.mark.parametrize("shape", [("resident_E8", 4096, 8, 2), ("generic_E16", 256, 16, 4),
+                                   ("gemm_E128", 512, 128, 8)])
+def test_route_counts_over_many_back_to_back_calls(moe, shape):
+    """Hundreds of moe_route calls of varying T on one stream with no host wait between them: the count
+    reduction hands state from one launch to the next (a ticket, sub-counters that are left at zero), so
+    every call's counts must equal the histogram of that call's own indices."""
+    import torch
+    name, d, E, k = shape
+    T_max = 3000
+    inp = wl.custom(name, T_max, d, 64, E, k, seed=23, wg_std=0.2, weights=False)
+    ctx = make_ctx(moe, inp)
+    x, rp, bias, _ = dev_inputs(ctx, inp, weights=False)
+    rng = np.random.default_rng(99)
+    Ts = [1, 16, 17, T_max, 255, 256, 257, 2, 1000] + rng.integers(1, T_max + 1, size=291).tolist()
+    print(f"route back-to-back {name}: {len(Ts)} calls, T in [1, {T_max}]", flush=True)
+    results = []
+    for T in Ts:
+        idx, w, counts = ctx.moe_route(x[:T], rp, bias)
+        results.append((T, idx, counts))
+    torch.cuda.synchronize()
+    for n, (T, idx, counts) in enumerate(results):
+        hist = np.bincount(idx.cpu().numpy().ravel(), minlength=E)
+        assert counts.cpu().numpy().tolist() == hist.tolist(), f"call {n} (T={T})"
+        assert hist.sum() == T * k
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------ permute
 PERM_CASES = [
     # name, T, E, k, e_lo, E_local
@@ -414,9 +441,25 @@ def test_layer_smaller_T_than_T_max_and_stage_events(moe):
     ctx.close()
 
 
-def test_staged_calls_equal_layer_forward(moe):
+STAGED_CASES = [
+    # the layer takes other launches than the staged calls between the router and the first GEMM (one-workgroup
+    # dispatch up to 512 tokens, histogram + work lists in one launch above) and, when the second GEMM is split
+    # along its reduction, adds the partial sums inside the combine: each of these must change no bit
+    ("one_workgroup_dispatch", lambda: wl.custom("staged", 400, 192, 256, 16, 4, seed=8, wg_std=0.08, w_std=0.06,
+                                                 e_lo=2, E_local=9)),
+    ("many_blocks", lambda: wl.custom("staged_blocks", 1500, 128, 256, 8, 2, seed=12, wg_std=0.08, w_std=0.06)),
+    ("many_blocks_ep", lambda: wl.custom("staged_ep", 2100, 128, 128, 64, 6, seed=13, wg_std=0.08, w_std=0.06,
+                                         e_lo=16, E_local=24)),
+    ("split_second_gemm", lambda: wl.custom("staged_split", 48, 256, 4096, 4, 2, seed=14, wg_std=0.05, w_std=0.03)),
+    ("split_many_blocks", lambda: wl.custom("staged_split2", 600, 256, 4096, 8, 2, seed=15, wg_std=0.05, w_std=0.03)),
+]
+
+
+@pytest.mark.parametrize("case", STAGED_CASES, ids=[c[0] for c in STAGED_CASES])
+def test_staged_calls_equal_layer_forward(moe, case):
     import torch
-    inp = wl.custom("staged", 400, 192, 256, 16, 4, seed=8, wg_std=0.08, w_std=0.06, e_lo=2, E_local=9)
+    print(f"staged case {case[0]}", flush=True)
+    inp = case[1]()
     s = inp.shape
     ctx = make_ctx(moe, inp)
     x, rp, bias, packed = dev_inputs(ctx, inp)
