@@ -421,8 +421,8 @@ moe_status moe_layer_forward(moe_ctx* c, const void* x, const void* rp, const fl
     if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
     const int nsplit = gemm_pick_split2(p, cap, s.E_local, s.d, s.f, c->part_bytes);
     const SchedArgs sa = gemm_sched_args(p, s.E_local, c->table1, c->table2, nsplit, cap, c->refused);
-    // up to a few hundred tokens the dispatch is one workgroup that counts for itself
-    const bool plan_counts = dispatch_plan_counts_itself(T);
+    // small batches: the dispatch launch counts the assignments itself and the router skips its count reduction
+    const bool plan_counts = dispatch_plan_counts_itself(T, s.k);
 
     if (ev) (void)hipEventRecord(ev[MOE_STAGE_ROUTE], st);
     hipError_t e = launch_route((const uint16_t*)x, (const uint16_t*)rp, bias, T, s.d, s.E, s.k, c->idx, c->w,

@@ -83,7 +83,7 @@ SchedArgs gemm_sched_args(const GemmPlan& p, int E_local, TileDesc* t1, TileDesc
 
 int gemm_sched_blocks(const GemmPlan& p) {
     int g = p.grid1 > p.grid2 ? p.grid1 : p.grid2;
-    int blocks = (g + 1023) / 1024;
+    int blocks = (g + 255) / 256;  // one entry per thread: an entry is a few thousand cycles of dependent integer work
     if (blocks < 1) blocks = 1;
     if (blocks > 64) blocks = 64;
     return blocks;

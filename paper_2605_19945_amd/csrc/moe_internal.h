@@ -138,9 +138,9 @@ SchedArgs gemm_sched_args(const GemmPlan& p, int E_local, TileDesc* t1, TileDesc
                           int32_t* refused);
 int gemm_sched_blocks(const GemmPlan& p);
 // Dispatch of the layer: offsets, row_of, tok_of and both work lists from idx (and the router's counts).
-// dispatch_plan_counts_itself(T): the launch counts the assignments itself (counts is an output, may be null,
+// dispatch_plan_counts_itself(T, k): the launch counts the assignments itself (counts is an output, may be null,
 // and the router need not count); otherwise counts[E] is the router's and is read.
-bool dispatch_plan_counts_itself(int T);
+bool dispatch_plan_counts_itself(int T, int k);
 hipError_t launch_dispatch_plan(const int32_t* idx, int T, int k, int E, int e_lo, int32_t* blockhist, int32_t* counts,
                                 int32_t* offsets, int32_t* row_of, int32_t* tok_of, const SchedArgs& a, int sched_blocks,
                                 hipStream_t st);

@@ -20,6 +20,22 @@
 
 constexpr int PB = 256;  // tokens per block (one token per thread)
 constexpr int PW = PB / 64;
+// A token's selected experts are fetched into registers in one go (all loads in flight together) before any
+// of them is used for an LDS atomic: written as load-then-atomic per entry, the k loads run one after the
+// other, a full memory round trip each.  Entries past KREG are read where they are used.
+constexpr int KREG = 8;
+static __device__ inline void load_topk(const int32_t* __restrict__ p, int k, int (&ev)[KREG]) {
+#pragma unroll
+    for (int j = 0; j < KREG; ++j) ev[j] = j < k ? p[j] : 0;
+}
+// f(j, expert) for every entry j < k of a token
+template <class F>
+static __device__ inline void for_topk(const int (&ev)[KREG], const int32_t* __restrict__ p, int k, F&& f) {
+#pragma unroll
+    for (int j = 0; j < KREG; ++j)
+        if (j < k) f(j, ev[j]);
+    for (int j = KREG; j < k; ++j) f(j, p[j]);
+}
 
 __global__ __launch_bounds__(PB) void permute_hist_kernel(const int32_t* __restrict__ idx, int T, int k,
                                                           int e_lo, int E_local,
@@ -108,8 +124,11 @@ __global__ __launch_bounds__(PB) void permute_rank_kernel(const int32_t* __restr
 // batches the three launches and the gaps between them cost more than the work (permute + work-list
 // stage at 64 tokens: 29 -> 17 us; from about four blocks on the three kernels are faster).
 constexpr int PF_BLOCKS = 2;
-// PLAN (plan_small_kernel of the layer): the same workgroup also counts the assignments of all E experts
-// (counts_out, may be null) and builds the work lists of the expert GEMMs from the offsets it has just formed.
+// PLAN (plan_small_kernel of the layer): workgroup 0 also counts the assignments of all E experts (counts_out,
+// may be null); the workgroups after it build the work lists of the expert GEMMs, each from a histogram of
+// its own over the few hundred tokens (cheaper than a second launch that waits for workgroup 0's offsets; one
+// work-list entry costs a thread about as long as the whole permutation, so they are spread over many
+// workgroups).
 template <bool PLAN>
 __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __restrict__ idx, int T, int k, int e_lo,
                                                            int E_local, int32_t* __restrict__ offsets,
@@ -122,18 +141,48 @@ __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __rest
     __shared__ int32_t tot[256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nblk = (T + PB - 1) / PB;
+    if constexpr (PLAN) {
+        if (blockIdx.x > 0) {
+            __shared__ int32_t s_scan[4];
+            int32_t* s_off = hist;  // [E_local + 1]
+            tot[tid] = 0;
+            __syncthreads();
+            int evs[PF_BLOCKS][KREG];
+#pragma unroll
+            for (int b = 0; b < PF_BLOCKS; ++b)
+                if (b * PB + tid < T) load_topk(idx + (size_t)(b * PB + tid) * k, k, evs[b]);
+#pragma unroll
+            for (int b = 0; b < PF_BLOCKS; ++b)
+                if (b * PB + tid < T)
+                    for_topk(evs[b], idx + (size_t)(b * PB + tid) * k, k, [&](int, int eg) {
+                        const int e = eg - e_lo;
+                        if (e >= 0 && e < E_local) atomicAdd(&tot[e], 1);
+                    });
+            __syncthreads();
+            const int incl = block_scan_incl(tot[tid], s_scan);  // tot is 0 beyond E_local
+            if (tid < E_local) s_off[tid + 1] = incl;
+            if (tid == 0) s_off[0] = 0;
+            __syncthreads();
+            schedule_tables(a, s_off, blockIdx.x - 1, gridDim.x - 1);
+            return;
+        }
+    }
+    int evs[PF_BLOCKS][KREG];  // this thread's tokens (one per block of PB) stay in registers throughout
+#pragma unroll
+    for (int b = 0; b < PF_BLOCKS; ++b)
+        if (b * PB + tid < T) load_topk(idx + (size_t)(b * PB + tid) * k, k, evs[b]);
     for (int o = tid; o < nblk * E_local; o += PB) hist[o] = 0;
     if (PLAN && counts_out != nullptr) wbase[tid] = 0;  // (free until the ranks) assignments per expert, all E
     __syncthreads();
-    for (int b = 0; b < nblk; ++b) {
+#pragma unroll
+    for (int b = 0; b < PF_BLOCKS; ++b) {
         const int t = b * PB + tid;
         if (t < T)
-            for (int j = 0; j < k; ++j) {
-                const int eg = idx[(size_t)t * k + j];
+            for_topk(evs[b], idx + (size_t)t * k, k, [&](int, int eg) {
                 if (PLAN && counts_out != nullptr) atomicAdd(&wbase[eg], 1);
                 const int e = eg - e_lo;
                 if (e >= 0 && e < E_local) atomicAdd(&hist[b * E_local + e], 1);
-            }
+            });
     }
     __syncthreads();
     if (PLAN && counts_out != nullptr && tid < E) counts_out[tid] = wbase[tid];
@@ -154,15 +203,17 @@ __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __rest
     }
     if (tid < E_local) offsets[tid + 1] = tot[tid];
     if (tid == 0) offsets[0] = 0;
-    for (int b = 0; b < nblk; ++b) {
+#pragma unroll
+    for (int b = 0; b < PF_BLOCKS; ++b) {
+        if (b >= nblk) break;  // uniform
         for (int o = tid; o < PW * E_local; o += PB) masks[o] = 0ull;
         __syncthreads();
         const int t = b * PB + tid;
         if (t < T)
-            for (int j = 0; j < k; ++j) {
-                const int e = idx[(size_t)t * k + j] - e_lo;
+            for_topk(evs[b], idx + (size_t)t * k, k, [&](int, int eg) {
+                const int e = eg - e_lo;
                 if (e >= 0 && e < E_local) atomicOr(&masks[wave * E_local + e], 1ull << lane);
-            }
+            });
         __syncthreads();
         for (int e = tid; e < E_local; e += PB) {
             int r = (e > 0 ? tot[e - 1] : 0) + hist[b * E_local + e];  // tot is the inclusive scan
@@ -175,25 +226,17 @@ __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __rest
         __syncthreads();
         if (t < T) {
             const unsigned long long below = (1ull << lane) - 1ull;
-            for (int j = 0; j < k; ++j) {
-                const int e = idx[(size_t)t * k + j] - e_lo;
+            for_topk(evs[b], idx + (size_t)t * k, k, [&](int j, int eg) {
+                const int e = eg - e_lo;
                 int r = -1;
                 if (e >= 0 && e < E_local) {
                     r = wbase[wave * E_local + e] + __popcll(masks[wave * E_local + e] & below);
                     tok_of[r] = t;
                 }
                 row_of[(size_t)t * k + j] = r;
-            }
+            });
         }
         __syncthreads();  // masks and wbase are rewritten for the next block
-    }
-    if constexpr (PLAN) {
-        // the exclusive prefix the scheduler wants: tot is the inclusive scan over the resident experts
-        int32_t* s_off = hist;  // (no longer read) [E_local + 1]
-        if (tid < E_local) s_off[tid + 1] = tot[tid];
-        if (tid == 0) s_off[0] = 0;
-        __syncthreads();
-        schedule_tables(a, s_off, 0, 1);
     }
 }
 
@@ -206,36 +249,83 @@ __global__ __launch_bounds__(PB) void permute_fused_kernel(const int32_t* __rest
 //                            permute_scan_kernel, redone by every block: nblk * E_local integers), then the ranks
 // two launches between the router and the first GEMM instead of four (histogram, scan, ranks, work lists), and
 // the work lists, the longest of them, are built next to the histograms instead of after the ranks.  Up to
-// PF_BLOCKS blocks of tokens everything happens in ONE workgroup (plan_small_kernel), which then also counts
-// the assignments itself, so that the router can skip its cross-workgroup count reduction.
+// PF_BLOCKS blocks of tokens everything happens in ONE launch (plan_small_kernel) whose first workgroup also
+// counts the assignments itself, so that the router can skip its cross-workgroup count reduction.
+constexpr int PLAN_COPIES = 32;
+constexpr int PLAN_OWN_COUNT_MAX = 16384;  // indices a work-list workgroup counts itself (64 per thread)
 __global__ __launch_bounds__(PB) void plan_kernel(const int32_t* __restrict__ idx, int T, int k, int e_lo, int nblk,
                                                   int32_t* __restrict__ blockhist,
-                                                  const int32_t* __restrict__ counts,
+                                                  const int32_t* __restrict__ counts_in, int E,
+                                                  int32_t* __restrict__ counts_out,
                                                   int32_t* __restrict__ offsets, SchedArgs a) {
     const int E_local = a.E_local;
     const int tid = threadIdx.x;
     if ((int)blockIdx.x < nblk) {
         __shared__ int32_t hist[256];
+        const int t = blockIdx.x * PB + tid;
+        int ev[KREG];
+        if (t < T) load_topk(idx + (size_t)t * k, k, ev);
         hist[tid] = 0;
         __syncthreads();
-        const int t = blockIdx.x * PB + tid;
         if (t < T)
-            for (int j = 0; j < k; ++j) {
-                const int e = idx[(size_t)t * k + j] - e_lo;
+            for_topk(ev, idx + (size_t)t * k, k, [&](int, int eg) {
+                const int e = eg - e_lo;
                 if (e >= 0 && e < E_local) atomicAdd(&hist[e], 1);
-            }
+            });
         __syncthreads();
         if (tid < E_local) blockhist[(size_t)blockIdx.x * E_local + tid] = hist[tid];
         return;
     }
     __shared__ int32_t s_off[257];
     __shared__ int32_t s_scan[4];
-    const int rows = tid < E_local ? counts[e_lo + tid] : 0;
+    const int part = blockIdx.x - nblk, parts = gridDim.x - nblk;
+    int rows;
+    if (counts_in != nullptr) {
+        rows = tid < E_local ? counts_in[e_lo + tid] : 0;
+    } else {
+        // No counts from the router (it skips its cross-workgroup reduction for batches this small): every
+        // work-list workgroup counts all T * k indices itself, into PLAN_COPIES histograms picked by thread
+        // so that few lanes meet on one address even with a handful of experts.
+        __shared__ int32_t h[PLAN_COPIES * 257];
+        int Ep = 8;
+        while (Ep < E) Ep <<= 1;
+        const int C = 2048 / Ep < PLAN_COPIES ? 2048 / Ep : PLAN_COPIES, stride = Ep + 1;
+        for (int o = tid; o < C * stride; o += PB) h[o] = 0;
+        __syncthreads();
+        int32_t* mine = h + (tid % C) * stride;
+        const int n = T * k, n4 = n >> 2;
+        const int4* idx4 = (const int4*)idx;  // (256-byte aligned workspace)
+        for (int base = 0; base < n4; base += 8 * PB) {
+            int4 v[8];  // eight 16-byte loads in flight per thread, then the atomics
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = base + u * PB + tid;
+                v[u] = i < n4 ? idx4[i] : make_int4(-1, -1, -1, -1);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (v[u].x >= 0) {
+                    atomicAdd(&mine[v[u].x], 1);
+                    atomicAdd(&mine[v[u].y], 1);
+                    atomicAdd(&mine[v[u].z], 1);
+                    atomicAdd(&mine[v[u].w], 1);
+                }
+        }
+        for (int i = 4 * n4 + tid; i < n; i += PB) atomicAdd(&mine[idx[i]], 1);
+        __syncthreads();
+        int all = 0;  // assignments to expert tid, resident or not
+        if (tid < E)
+            for (int c = 0; c < C; ++c) all += h[c * stride + tid];
+        if (part == 0 && counts_out != nullptr && tid < E) counts_out[tid] = all;
+        __syncthreads();
+        if (tid < E) h[tid] = all;
+        __syncthreads();
+        rows = tid < E_local ? h[e_lo + tid] : 0;
+    }
     const int incl = block_scan_incl(rows, s_scan);
     if (tid < E_local) s_off[tid + 1] = incl;
     if (tid == 0) s_off[0] = 0;
     __syncthreads();
-    const int part = blockIdx.x - nblk, parts = gridDim.x - nblk;
     if (part == 0)
         for (int i = tid; i <= E_local; i += PB) offsets[i] = s_off[i];
     schedule_tables(a, s_off, part, parts);
@@ -249,6 +339,10 @@ __global__ __launch_bounds__(PB) void permute_rank2_kernel(const int32_t* __rest
     int32_t* wbase = (int32_t*)(masks + PW * E_local);     // [PW][E_local] rows of e in earlier waves
     int32_t* before = wbase + PW * E_local;                // [E_local] assignments to e in earlier blocks
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t = blockIdx.x * PB + tid;
+    int ev[KREG];
+    if (t < T) load_topk(idx + (size_t)t * k, k, ev);
+    const int off_mine = tid < E_local ? offsets[tid] : 0;
     for (int o = tid; o < PW * E_local; o += PB) masks[o] = 0ull;
     for (int e = tid; e < E_local; e += PB) before[e] = 0;
     __syncthreads();
@@ -261,15 +355,14 @@ __global__ __launch_bounds__(PB) void permute_rank2_kernel(const int32_t* __rest
         for (int b = g; b < (int)blockIdx.x; b += G) sum += blockhist[(size_t)b * E_local + e_mine];
         if (sum != 0) atomicAdd(&before[e_mine], sum);
     }
-    const int t = blockIdx.x * PB + tid;
     if (t < T)
-        for (int j = 0; j < k; ++j) {
-            int e = idx[(size_t)t * k + j] - e_lo;
+        for_topk(ev, idx + (size_t)t * k, k, [&](int, int eg) {
+            const int e = eg - e_lo;
             if (e >= 0 && e < E_local) atomicOr(&masks[wave * E_local + e], 1ull << lane);
-        }
+        });
     __syncthreads();
-    for (int e = tid; e < E_local; e += PB) {
-        int run = offsets[e] + before[e];
+    for (int e = tid; e < E_local; e += PB) {  // (E_local <= PB: e == tid)
+        int run = off_mine + before[e];
 #pragma unroll
         for (int ww = 0; ww < PW; ++ww) {
             wbase[ww * E_local + e] = run;
@@ -279,15 +372,15 @@ __global__ __launch_bounds__(PB) void permute_rank2_kernel(const int32_t* __rest
     __syncthreads();
     if (t < T) {
         const unsigned long long below = (1ull << lane) - 1ull;
-        for (int j = 0; j < k; ++j) {
-            int e = idx[(size_t)t * k + j] - e_lo;
+        for_topk(ev, idx + (size_t)t * k, k, [&](int j, int eg) {
+            const int e = eg - e_lo;
             int r = -1;
             if (e >= 0 && e < E_local) {
                 r = wbase[wave * E_local + e] + __popcll(masks[wave * E_local + e] & below);
                 tok_of[r] = t;
             }
             row_of[(size_t)t * k + j] = r;
-        }
+        });
     }
 }
 
@@ -308,21 +401,23 @@ hipError_t launch_permute(const int32_t* idx, int T, int k, int e_lo, int E_loca
     return hipGetLastError();
 }
 
-bool dispatch_plan_counts_itself(int T) { return (T + PB - 1) / PB <= PF_BLOCKS; }
+bool dispatch_plan_counts_itself(int T, int k) { return (long long)T * k <= PLAN_OWN_COUNT_MAX; }
 
 // Permutation plus work lists of the layer (see plan_kernel).  counts: the router's per-expert counts over all E
-// experts; with dispatch_plan_counts_itself(T) they are an OUTPUT here (or null), otherwise an input.
+// experts; with dispatch_plan_counts_itself(T, k) they are an OUTPUT here (or null), otherwise an input.
 hipError_t launch_dispatch_plan(const int32_t* idx, int T, int k, int E, int e_lo, int32_t* blockhist, int32_t* counts,
                                 int32_t* offsets, int32_t* row_of, int32_t* tok_of, const SchedArgs& a, int sched_blocks,
                                 hipStream_t st) {
     const int nblk = (T + PB - 1) / PB, E_local = a.E_local;
     if (nblk <= PF_BLOCKS) {
-        hipLaunchKernelGGL(permute_fused_kernel<true>, dim3(1), dim3(PB), 0, st, idx, T, k, e_lo, E_local, offsets,
+        hipLaunchKernelGGL(permute_fused_kernel<true>, dim3(1 + sched_blocks), dim3(PB), 0, st, idx, T, k, e_lo, E_local, offsets,
                            row_of, tok_of, E, counts, a);
         return hipGetLastError();
     }
+    const bool own = dispatch_plan_counts_itself(T, k);
     hipLaunchKernelGGL(plan_kernel, dim3(nblk + sched_blocks), dim3(PB), 0, st, idx, T, k, e_lo, nblk, blockhist,
-                       (const int32_t*)counts, offsets, a);
+                       own ? (const int32_t*)nullptr : (const int32_t*)counts, E, own ? counts : (int32_t*)nullptr,
+                       offsets, a);
     const size_t smem = (size_t)PW * E_local * (sizeof(unsigned long long) + sizeof(int32_t)) + (size_t)E_local * 4;
     hipLaunchKernelGGL(permute_rank2_kernel, dim3(nblk), dim3(PB), smem, st, idx, T, k, e_lo, E_local,
                        (const int32_t*)blockhist, (const int32_t*)offsets, row_of, tok_of);

@@ -282,6 +282,8 @@ __global__ __launch_bounds__(RR_NW * 64) void route_resident_kernel(
     const int steps = d / (32 * RR_NW);  // K steps of 32 per wavefront, <= RR_MAXS
     const int groups = (T + ROUTE_TOK - 1) / ROUTE_TOK;
     if (tid < 8) hist[tid] = 0;
+    // fetched up front: read where it is added, it would be one more memory round trip behind the reduction
+    const float bias_mine = (bias != nullptr && tid < 8 * ROUTE_TOK && (tid >> 4) < E) ? bias[tid >> 4] : 0.f;
 
     const size_t koff = (size_t)wave * steps * 32 + 8 * (lane >> 4);
     bf16x8_t wf[RR_MAXS], xf[RR_MAXS], xn[RR_MAXS];
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(RR_NW * 64) void route_resident_kernel(
             float s = 0.f;
 #pragma unroll
             for (int ww = 0; ww < RR_NW; ++ww) s += part[ww][e][t] + part[ww][e + 8][t];  // high + low term
-            if (bias != nullptr && e < E) s += bias[e];
+            s += bias_mine;
             logit[t][e] = s;
         }
         __syncthreads();
