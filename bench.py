@@ -156,6 +156,105 @@ def hbm_stages(moe, s, T, seed, iters=30):
             for k, (b, ms) in out.items()}
 
 
+class ClockSampler:
+    """Shader clock (MHz) while a load runs, read from `rocm-smi --showclocks --json` a few times a second in a
+    thread of its own.  The device lowers its clock to stay inside its power limit, so the clock a kernel
+    sustains is part of what bounds it."""
+
+    def __init__(self, period=0.15):
+        self.period, self.samples, self._stop, self._th = period, [], False, None
+
+    def _run(self):
+        import subprocess
+        while not self._stop:
+            try:
+                r = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=5)
+                for card in json.loads(r.stdout).values():
+                    for key, val in card.items():
+                        if "sclk" in key.lower() and "speed" in key.lower():
+                            self.samples.append(float(str(val).strip("()Mhz ")))
+            except Exception:
+                pass
+            time.sleep(self.period)
+
+    def __enter__(self):
+        import threading
+        self._th = threading.Thread(target=self._run, daemon=True)
+        self._th.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        self._th.join()
+
+    def mean(self):
+        v = self.samples[2:] if len(self.samples) > 4 else self.samples   # the first readings predate the load
+        return sum(v) / len(v) if v else None
+
+
+def run_gemm_trail(moe, ctx, s, cnt, packed, secs):
+    """What bounds the grouped GEMM: rate and sustained shader clock of (a) an MFMA-only kernel, (b) the two
+    expert GEMMs of this library on the workload's per-expert loads, (c) the vendor library's dense GEMM
+    (torch.matmul, i.e. hipBLASLt) on ONE matrix of the same total size, in both operand layouts.  Every load
+    loops for `secs` seconds while the clock is sampled."""
+    import torch
+    rows = []
+
+    def loop(name, fn, flop, per_sync=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        with ClockSampler() as cs:
+            t0 = time.perf_counter()
+            n = 0
+            while time.perf_counter() - t0 < secs:
+                for _ in range(per_sync):
+                    fn()
+                torch.cuda.synchronize()
+                n += per_sync
+            dt = time.perf_counter() - t0
+        rate = flop * n / dt / 1e12
+        rows.append({"load": name, "TFLOPs": rate, "sclk_MHz": cs.mean(), "ms": dt / n * 1e3})
+
+    # (a) MFMA only: the library's own rate kernel reports its rate; sample the clock around it
+    with ClockSampler() as cs:
+        t0 = time.perf_counter()
+        rates = []
+        while time.perf_counter() - t0 < secs:
+            rates.append(moe.moe_measure_mfma_rate(2500, 5))
+    rows.append({"load": "MFMA only (v_mfma_f32_32x32x16_bf16, no loads)", "TFLOPs": sum(rates) / len(rates),
+                 "sclk_MHz": cs.mean(), "ms": None})
+    # (b) this library: both expert GEMMs on the workload's loads (rows already expert-contiguous)
+    local = [int(c) for c in cnt[s.e_lo:s.e_lo + s.E_local]]
+    A = sum(local)
+    off = torch.tensor([0] + list(__import__("itertools").accumulate(local)), dtype=torch.int32, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    xp = torch.randn(A, s.d, device="cuda", generator=g).bfloat16()
+    y = torch.empty(A, s.d, dtype=torch.bfloat16, device="cuda")
+    loop(f"moe_grouped_ffn, loads {local}", lambda: ctx.moe_grouped_ffn(xp, off, A, packed, y=y),
+         6.0 * A * s.d * s.f)
+    # (c) vendor dense GEMM of the same size: [A, d] x [d, 2f] and [A, f] x [f, d]
+    Wa = (torch.randn(2 * s.f, s.d, device="cuda", generator=g) * 0.02).bfloat16()
+    loop(f"torch.matmul {A}x{2 * s.f}x{s.d}, weights [2f, d] (k contiguous)", lambda: xp @ Wa.t(),
+         4.0 * A * s.d * s.f)
+    Wb = Wa.t().contiguous()
+    loop(f"torch.matmul {A}x{2 * s.f}x{s.d}, weights [d, 2f] (n contiguous)", lambda: xp @ Wb,
+         4.0 * A * s.d * s.f)
+    del Wa, Wb
+    h = torch.randn(A, s.f, device="cuda", generator=g).bfloat16()
+    Wc = (torch.randn(s.d, s.f, device="cuda", generator=g) * 0.02).bfloat16()
+    loop(f"torch.matmul {A}x{s.d}x{s.f}, weights [d, f] (k contiguous)", lambda: h @ Wc.t(), 2.0 * A * s.d * s.f)
+    for r in rows:
+        clk = r["sclk_MHz"]
+        r["TFLOPs_per_GHz"] = r["TFLOPs"] / clk * 1e3 if clk else None
+        log(f"gemm-trail: {r['load']:78s} {r['TFLOPs']:7.0f} TFLOP/s at "
+            + (f"{clk:5.0f} MHz = {r['TFLOPs_per_GHz']:.0f} TFLOP/s per GHz" if clk else "(no clock reading)"))
+    log(f"gemm-trail: the published peak is {PEAK_BF16_TFLOPS:.0f} TFLOP/s at 2400 MHz = "
+        f"{PEAK_BF16_TFLOPS / 2.4:.0f} TFLOP/s per GHz")
+    return rows
+
+
 def cpu_baseline(inp, sample_tokens):
     """The oracle as it stands, on a bounded sample of the workload's tokens, on the host cores."""
     import numpy as np
@@ -385,6 +484,10 @@ def main():
     ap.add_argument("--profile-iters", type=int, default=10)
     ap.add_argument("--gem-demo", action="store_true",
                     help="profile -> trace -> mapping search on emulated GPU variability (paper Steps 1-3)")
+    ap.add_argument("--gemm-trail", action="store_true",
+                    help="rate and sustained shader clock of an MFMA-only load, of this library's expert GEMMs and "
+                         "of the vendor library's dense GEMM of the same size (what bounds the grouped GEMM)")
+    ap.add_argument("--trail-secs", type=float, default=4.0)
     ap.add_argument("--curve", action="store_true")
     ap.add_argument("--curve-loads", default="512,1024,2048,4096,8192")
     ap.add_argument("--curve-steps", type=int, default=20)
@@ -474,6 +577,8 @@ def main():
         log(f"sustained MFMA-only rate: {sustained:.0f} TFLOP/s = {100 * sustained / PEAK_BF16_TFLOPS:.1f} % of the "
             f"{PEAK_BF16_TFLOPS:.0f} TFLOP/s peak; GEMM1 reaches {100 * g1 / sustained:.1f} % of it")
         result["roofline"]["sustained_mfma_only"] = sustained
+    if args.gemm_trail:
+        result["roofline"]["gemm_trail"] = run_gemm_trail(moe, ctx, s, cnt, packed, args.trail_secs)
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)

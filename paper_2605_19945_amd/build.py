@@ -12,7 +12,8 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libmoe_gfx950.so")
 SOURCES = ["moe_api.hip", "moe_route.hip", "moe_permute.hip", "moe_pack.hip", "moe_gemm.hip", "moe_gemm_swiglu.hip",
-           "moe_gemm_plain.hip", "moe_gemm_pairsum.hip", "moe_gemm_partial.hip", "moe_place.hip"]
+           "moe_gemm_plain.hip", "moe_gemm_pairsum.hip", "moe_gemm_partial.hip", "moe_gemm_swiglu_stream.hip",
+           "moe_gemm_plain_stream.hip", "moe_gemm_partial_stream.hip", "moe_place.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -319,6 +319,7 @@ static moe_status run_ffn(moe_ctx* c, int cls, const uint16_t* X, const int32_t*
     } else {
         p = gemm_make_plan(cls, n_rows_cap, s.E_local, s.d, s.f);
         if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
+        p.w_stream = gemm_pick_stream(cls, (double)n_rows_cap / s.E_local);
         nsplit = gemm_pick_split2(p, n_rows_cap, s.E_local, s.d, s.f, c->part_bytes);
         // offsets[E_local] = the rows actually present
         e = launch_schedule(p, offsets, s.E_local, c->table1, c->table2, nsplit, n_rows_cap, c->refused, st);
@@ -417,8 +418,9 @@ moe_status moe_layer_forward(moe_ctx* c, const void* x, const void* rp, const fl
     // everything the host decides is decided before the first launch: tile class, work-list sizes, splits
     const int64_t cap = moe_rows_capacity(&s, T);
     const int cls = c->forced_cls >= 0 ? c->forced_cls : gemm_pick_class((double)T * s.k / s.E);
-    const GemmPlan p = gemm_make_plan(cls, cap, s.E_local, s.d, s.f);
+    GemmPlan p = gemm_make_plan(cls, cap, s.E_local, s.d, s.f);
     if (p.grid1 > c->table1_cap || p.grid2 > c->table2_cap) return MOE_ERR_WORKSPACE_TOO_SMALL;
+    p.w_stream = gemm_pick_stream(cls, (double)T * s.k / s.E);
     const int nsplit = gemm_pick_split2(p, cap, s.E_local, s.d, s.f, c->part_bytes);
     const SchedArgs sa = gemm_sched_args(p, s.E_local, c->table1, c->table2, nsplit, cap, c->refused);
     // small batches: the dispatch launch counts the assignments itself and the router skips its count reduction

@@ -267,7 +267,12 @@ static __device__ inline void wait_vmcnt_rt(int n) {
 // length): workgroup (x, y) reduces over elements [y*K, (y+1)*K) of the K_total = gridDim.y * K long
 // reduction dimension and writes its partial result c_split_bytes behind that of split y-1; the
 // consumer adds the partial results in a fixed order.
-template <int BM, int NSX, int EPI, int NW>
+// W_STREAM: the weight loads carry the non-temporal hint.  A launch in which every expert has a single row
+// tile reads each weight once; plain loads then reach about 6.4 TB/s of the 8 TB/s HBM peak on this device and
+// hinted ones about 7.2 TB/s (read-only streaming kernel, 1.9 GB).  Launches whose row tiles share weight
+// panels through the L2 lose with the hint (Mixtral shape, 1024 rows per expert: +2.8 % time), so it is a
+// variant picked per launch.
+template <int BM, int NSX, int EPI, int NW, bool W_STREAM>
 __global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
                                                       const int32_t* __restrict__ row_map,
                                                       const uint16_t* __restrict__ Wf, int Np, int K,
@@ -364,10 +369,17 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* _
             constexpr int kk = decltype(j_c)::value / FN, a = decltype(j_c)::value % FN;
             u32x4_t v;
             const char* base = wsrc[a] + (size_t)kt * (KK * 1024);
-            asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"
-                         : "=v"(v)
-                         : "v"(wlane), "s"(base), "n"(kk * 1024)
-                         : "memory");
+            if constexpr (W_STREAM) {
+                asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt"
+                             : "=v"(v)
+                             : "v"(wlane), "s"(base), "n"(kk * 1024)
+                             : "memory");
+            } else {
+                asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"
+                             : "=v"(v)
+                             : "v"(wlane), "s"(base), "n"(kk * 1024)
+                             : "memory");
+            }
             wr[BUF][kk][a] = __builtin_bit_cast(bf16x8_t, v);
         };
         // prologue: weights of stages 0, 1 and tokens of stages 0 .. DX-1, oldest needs first
@@ -544,47 +556,56 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* _
     V(5, 64, 4, 2)
 #endif
 
-template <int BM, int NSX, int EPI, int NW>
+template <int BM, int NSX, int EPI, int NW, bool WS>
 struct Variant {
     static constexpr size_t smem = (size_t)NSX * BM * 64 * 2;
     static hipError_t set_attr() {
-        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, NSX, EPI, NW>,
+        return hipFuncSetAttribute((const void*)grouped_gemm_kernel<BM, NSX, EPI, NW, WS>,
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     // K is the reduction length of ONE split; nsplit = 1 for the expert GEMMs
     static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wf,
                              int Np, int K, uint16_t* C, int ldc, const TileDesc* table, int nsplit,
                              size_t c_split_bytes, hipStream_t st) {
-        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI, NW>), dim3(grid, nsplit), dim3(NW * 64), smem, st, X,
-                           ldx, row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
+        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI, NW, WS>), dim3(grid, nsplit), dim3(NW * 64), smem, st,
+                           X, ldx, row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
         return hipGetLastError();
     }
 };
 
-// Defines gemm_set_attr_<name>() and gemm_launch_<name>(cls, ...) for one epilogue; each epilogue
-// is compiled in a translation unit of its own so that the units build in parallel.
-#define MOE_GEMM_INSTANTIATE(name, EPI)                                                                       \
-    hipError_t gemm_set_attr_##name() {                                                                       \
-        hipError_t err;                                                                                       \
-        FOR_EACH_VARIANT(MOE_GEMM_SET_ATTR_##EPI)                                                             \
-        return hipSuccess;                                                                                    \
-    }                                                                                                         \
+template <int EPI, bool WS>
+static hipError_t gemm_set_attr_all() {
+    hipError_t err;
+#define V(id, bm, ns, nw)                               \
+    err = Variant<bm, ns, EPI, nw, WS>::set_attr();     \
+    if (err != hipSuccess) return err;
+    FOR_EACH_VARIANT(V)
+#undef V
+    return hipSuccess;
+}
+
+template <int EPI, bool WS>
+static hipError_t gemm_launch_any(int cls, int grid, const uint16_t* X, int ldx, const int32_t* row_map,
+                                  const uint16_t* Wf, int Np, int K, uint16_t* C, int ldc, const TileDesc* table,
+                                  int nsplit, size_t c_split_bytes, hipStream_t st) {
+    switch (cls) {
+#define V(id, bm, ns, nw)                                                                                     \
+    case id:                                                                                                  \
+        return Variant<bm, ns, EPI, nw, WS>::launch(grid, X, ldx, row_map, Wf, Np, K, C, ldc, table, nsplit,  \
+                                                    c_split_bytes, st);
+        FOR_EACH_VARIANT(V)
+#undef V
+    }
+    return hipErrorInvalidValue;
+}
+
+// Defines gemm_set_attr_<name>() and gemm_launch_<name>(cls, ...) for one epilogue and one kind of weight load;
+// each is compiled in a translation unit of its own so that the units build in parallel.
+#define MOE_GEMM_INSTANTIATE(name, EPI, WS)                                                                   \
+    hipError_t gemm_set_attr_##name() { return gemm_set_attr_all<EPI, WS>(); }                                \
     hipError_t gemm_launch_##name(int cls, int grid, const uint16_t* X, int ldx, const int32_t* row_map,      \
                                   const uint16_t* Wf, int Np, int K, uint16_t* C, int ldc,                    \
                                   const TileDesc* table, int nsplit, size_t c_split_bytes, hipStream_t st) {  \
-        switch (cls) { FOR_EACH_VARIANT(MOE_GEMM_CASE_##EPI) }                                                \
-        return hipErrorInvalidValue;                                                                          \
+        return gemm_launch_any<EPI, WS>(cls, grid, X, ldx, row_map, Wf, Np, K, C, ldc, table, nsplit,         \
+                                        c_split_bytes, st);                                                   \
     }
-#define MOE_GEMM_SET_ATTR(EPI, bm, ns, nw)        \
-    err = Variant<bm, ns, EPI, nw>::set_attr();   \
-    if (err != hipSuccess) return err;
-#define MOE_GEMM_CASE(EPI, id, bm, ns, nw) \
-    case id: return Variant<bm, ns, EPI, nw>::launch(grid, X, ldx, row_map, Wf, Np, K, C, ldc, table, nsplit, c_split_bytes, st);
-#define MOE_GEMM_SET_ATTR_EPI_PLAIN(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_PLAIN, bm, ns, nw)
-#define MOE_GEMM_SET_ATTR_EPI_SWIGLU(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_SWIGLU, bm, ns, nw)
-#define MOE_GEMM_SET_ATTR_EPI_PAIR_SUM_F32(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_PAIR_SUM_F32, bm, ns, nw)
-#define MOE_GEMM_SET_ATTR_EPI_PARTIAL_F32(id, bm, ns, nw) MOE_GEMM_SET_ATTR(EPI_PARTIAL_F32, bm, ns, nw)
-#define MOE_GEMM_CASE_EPI_PLAIN(id, bm, ns, nw) MOE_GEMM_CASE(EPI_PLAIN, id, bm, ns, nw)
-#define MOE_GEMM_CASE_EPI_SWIGLU(id, bm, ns, nw) MOE_GEMM_CASE(EPI_SWIGLU, id, bm, ns, nw)
-#define MOE_GEMM_CASE_EPI_PAIR_SUM_F32(id, bm, ns, nw) MOE_GEMM_CASE(EPI_PAIR_SUM_F32, id, bm, ns, nw)
-#define MOE_GEMM_CASE_EPI_PARTIAL_F32(id, bm, ns, nw) MOE_GEMM_CASE(EPI_PARTIAL_F32, id, bm, ns, nw)

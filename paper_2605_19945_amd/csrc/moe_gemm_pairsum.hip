@@ -2,4 +2,4 @@
 #define MOE_GEMM_NO_TALL_TILE
 #include "moe_gemm_kernel.h"
 
-MOE_GEMM_INSTANTIATE(pairsum, EPI_PAIR_SUM_F32)
+MOE_GEMM_INSTANTIATE(pairsum, EPI_PAIR_SUM_F32, false)

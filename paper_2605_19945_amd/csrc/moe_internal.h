@@ -41,6 +41,7 @@ struct GemmPlan {
     int mt_max;      // upper bound on the number of row tiles
     int nt1, nt2;    // weight-row tiles of GEMM1 (2f packed rows) and GEMM2 (d rows)
     int grid1, grid2;
+    bool w_stream;   // weight loads carry the non-temporal hint (gemm_pick_stream)
 };
 
 constexpr int MOE_EVENT_RING = 64;
@@ -125,6 +126,7 @@ hipError_t launch_combine(const uint16_t* y, const int32_t* row_of, const float*
 GemmPlan gemm_make_plan(int cls, int64_t n_rows_cap, int E_local, int d, int f);
 int gemm_pick_class(double expected_rows_per_expert);
 int gemm_class_rows(int cls);
+bool gemm_pick_stream(int cls, double expected_rows_per_expert);
 hipError_t gemm_init_attributes();
 int router_gemm_grid_max(int T_max, int Rp);
 hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int d, int Rp, float* logits, int ldl,
