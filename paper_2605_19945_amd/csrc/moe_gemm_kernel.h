@@ -272,13 +272,13 @@ static __device__ inline void wait_vmcnt_rt(int n) {
 // hinted ones about 7.2 TB/s (read-only streaming kernel, 1.9 GB).  Launches whose row tiles share weight
 // panels through the L2 lose with the hint (Mixtral shape, 1024 rows per expert: +2.8 % time), so it is a
 // variant picked per launch.
+// gemm_tile: one work item (table entry bx) by one workgroup.
 template <int BM, int NSX, int EPI, int NW, bool W_STREAM>
-__global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
-                                                      const int32_t* __restrict__ row_map,
-                                                      const uint16_t* __restrict__ Wf, int Np, int K,
-                                                      uint16_t* __restrict__ C, int ldc,
-                                                      const TileDesc* __restrict__ table,
-                                                      size_t c_split_bytes) {
+static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restrict__ X, int ldx,
+                                                 const int32_t* __restrict__ row_map,
+                                                 const uint16_t* __restrict__ Wf, int Np, int K,
+                                                 uint16_t* __restrict__ C, int ldc,
+                                                 const TileDesc* __restrict__ table, size_t c_split_bytes) {
     constexpr int BN = 64 * NW, BK = 64, TN = BN / NW, FN = TN / 32, FM = BM / 32;
     constexpr int CH = BK / 8;   // 16-byte chunks per staged token row
     constexpr int RPL = 64 / CH; // rows covered by one wave-level load
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* _
 
     extern __shared__ u32x4_t lds[];  // [NSX][STAGE]
 
-    const TileDesc td = table[blockIdx.x];
+    const TileDesc td = table[bx];
     if (td.rows <= 0) return;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -556,6 +556,35 @@ __global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* _
     V(5, 64, 4, 2)
 #endif
 
+// Workgroup x takes the entries x, x + gridDim.x, ... of the work list.  Every class but the decode class is
+// launched with one workgroup per entry: the hardware then hands the next entry to whichever compute unit is
+// free, which balances tiles of unequal height (looping over a fixed share instead costs 3.5 % on the Mixtral
+// shape at 1024 rows per expert and 13 % on ragged fine-grained loads).  The decode class has equal items
+// that only stream weights; there a workgroup that stays resident saves the placement of a new one (about
+// 5 us each): first expert GEMM of the Mixtral shape at 16 rows per expert, 1792 items on 1024 resident
+// workgroups, 310 -> 298 us.  The barrier between two items keeps the next item's token loads out of the ring
+// until every wavefront has read back its staged output.
+template <int BM, int NSX, int EPI, int NW, bool W_STREAM>
+__global__ __launch_bounds__(NW * 64) void grouped_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
+                                                               const int32_t* __restrict__ row_map,
+                                                               const uint16_t* __restrict__ Wf, int Np, int K,
+                                                               uint16_t* __restrict__ C, int ldc,
+                                                               const TileDesc* __restrict__ table,
+                                                               size_t c_split_bytes, int n_entries) {
+    if constexpr (NW == 2) {
+        for (int b = blockIdx.x; b < n_entries; b += gridDim.x) {
+            gemm_tile<BM, NSX, EPI, NW, W_STREAM>(b, X, ldx, row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
+            // LDS reads only: the output stores need not have completed (a full __syncthreads() would also
+            // wait for them, and a workgroup that waits for its last stores holds its compute unit longer)
+            if (b + (int)gridDim.x < n_entries) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+    } else {
+        // no loop in the code of the other classes: the compiler would keep the lane-dependent values it can
+        // hoist out of it in registers for the whole kernel, and the tall tiles have none to spare
+        gemm_tile<BM, NSX, EPI, NW, W_STREAM>(blockIdx.x, X, ldx, row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
+    }
+}
+
 template <int BM, int NSX, int EPI, int NW, bool WS>
 struct Variant {
     static constexpr size_t smem = (size_t)NSX * BM * 64 * 2;
@@ -567,8 +596,10 @@ struct Variant {
     static hipError_t launch(int grid, const uint16_t* X, int ldx, const int32_t* row_map, const uint16_t* Wf,
                              int Np, int K, uint16_t* C, int ldc, const TileDesc* table, int nsplit,
                              size_t c_split_bytes, hipStream_t st) {
-        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI, NW, WS>), dim3(grid, nsplit), dim3(NW * 64), smem, st,
-                           X, ldx, row_map, Wf, Np, K, C, ldc, table, c_split_bytes);
+        constexpr int RESIDENT = 256 * 4;  // decode class: four workgroups fit a compute unit
+        const int gx = (NW == 2 && grid > RESIDENT) ? RESIDENT : grid;
+        hipLaunchKernelGGL((grouped_gemm_kernel<BM, NSX, EPI, NW, WS>), dim3(gx, nsplit), dim3(NW * 64), smem, st,
+                           X, ldx, row_map, Wf, Np, K, C, ldc, table, c_split_bytes, grid);
         return hipGetLastError();
     }
 };
