@@ -542,6 +542,17 @@ def main():
         f"({g2 / PEAK_BF16_TFLOPS:.1%}); route {route_gbs:.0f} GB/s, combine {combine_gbs:.0f} GB/s "
         f"(stage intervals include launch gaps); tile rows {ctx.moe_tile_rows()}; counts {cnt.tolist()}")
 
+    # the dominant kernel (GEMM1) against the roofline that bounds it at this load: MFMA, or HBM when the
+    # launch mostly streams the weights of the loaded experts (bytes: W1|W3 of every expert with rows, the
+    # token rows in, the activated rows out)
+    loaded = int((cnt[s.e_lo:s.e_lo + s.E_local] > 0).sum())
+    g1_bytes = loaded * 2.0 * s.f * s.d * 2 + A_local * s.d * 2.0 + A_local * s.f * 2.0
+    g1_hbm_gbs = g1_bytes / stages["gemm1"] / 1e6
+    g1_flop = 4.0 * A_local * s.d * s.f
+    hbm_bound = g1_bytes / (PEAK_HBM_GBS * 1e9) > g1_flop / (PEAK_BF16_TFLOPS * 1e12)
+    if hbm_bound:
+        log(f"gemm1 is bound by weight streaming at this load: {g1_bytes / 1e9:.3f} GB in {stages['gemm1'] * 1e3:.0f} us = "
+            f"{g1_hbm_gbs:.0f} GB/s ({g1_hbm_gbs / PEAK_HBM_GBS:.1%} of HBM peak)")
     result = {
         "metric": "MoE layer TFLOP/s + latency vs per-GPU token load (Mixtral-8x7B shape, 1 GPU)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -550,8 +561,12 @@ def main():
         "config": {"workload": inp.name, "T": s.T, "d": s.d, "f": s.f, "E": s.E, "k": s.k,
                    "E_local": s.E_local, "local_assignments": A_local, "tile_rows": ctx.moe_tile_rows(),
                    "stages_ms": stages},
-        "roofline": {"bound": "mfma", "kernel": "grouped_gemm_kernel<SwiGLU> (GEMM1)", "achieved": g1,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": g1 / PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "hbm" if hbm_bound else "mfma", "kernel": "grouped_gemm_kernel<SwiGLU> (GEMM1)",
+                     "achieved": g1_hbm_gbs if hbm_bound else g1,
+                     "peak": PEAK_HBM_GBS if hbm_bound else PEAK_BF16_TFLOPS,
+                     "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                     "frac": g1_hbm_gbs / PEAK_HBM_GBS if hbm_bound else g1 / PEAK_BF16_TFLOPS,
+                     "mfma_frac": g1 / PEAK_BF16_TFLOPS, "hbm_frac": g1_hbm_gbs / PEAK_HBM_GBS,
                      "traffic": profiled_traffic(inp.name, "gemm1") if args.tile_class < 0 else None,
                      "traffic_source": "committed rocprofv3 --pmc summary of this command (profiles/), not this run",
                      "gemm2": {"achieved": g2, "frac": g2 / PEAK_BF16_TFLOPS}},
@@ -577,6 +592,14 @@ def main():
         log(f"sustained MFMA-only rate: {sustained:.0f} TFLOP/s = {100 * sustained / PEAK_BF16_TFLOPS:.1f} % of the "
             f"{PEAK_BF16_TFLOPS:.0f} TFLOP/s peak; GEMM1 reaches {100 * g1 / sustained:.1f} % of it")
         result["roofline"]["sustained_mfma_only"] = sustained
+        # the same for HBM: what a read-only streaming kernel reaches over the expert weights
+        hbm = {"bytes": packed.numel() * packed.element_size(),
+               "plain_GBps": moe.moe_measure_hbm_read_rate(packed, nontemporal=False),
+               "nontemporal_GBps": moe.moe_measure_hbm_read_rate(packed, nontemporal=True)}
+        log(f"sustained read-only streaming over the {hbm['bytes'] / 1e9:.2f} GB of expert weights: "
+            f"{hbm['plain_GBps']:.0f} GB/s with plain loads, {hbm['nontemporal_GBps']:.0f} GB/s with the "
+            f"non-temporal hint ({100 * hbm['nontemporal_GBps'] / PEAK_HBM_GBS:.0f} % of the {PEAK_HBM_GBS:.0f} GB/s peak)")
+        result["roofline"]["sustained_hbm_read"] = hbm
     if args.gemm_trail:
         result["roofline"]["gemm_trail"] = run_gemm_trail(moe, ctx, s, cnt, packed, args.trail_secs)
     if args.calibrate_copy:

@@ -27,7 +27,7 @@
  *   - The calls that take a stream only launch kernels on it (no memsets, no allocation, no host
  *     synchronisation), so they may be recorded under stream capture and replayed as a HIP graph; the
  *     exceptions are contexts created with MOE_FLAG_STAGE_EVENTS (they record events), moe_profile_ffn
- *     and moe_measure_mfma_rate (they time and wait).
+ *     moe_measure_mfma_rate and moe_measure_hbm_read_rate (they time and wait).
  */
 #ifndef MOE_H_
 #define MOE_H_
@@ -262,6 +262,16 @@ moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
  * `launches` >= 1 launches of iters_per_wave * 64 MFMAs per wavefront on `stream`, times them with events and waits for them.
  * tflops: host pointer.  Errors: MOE_ERR_INVALID_ARG, MOE_ERR_DEVICE. */
 moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops /* host */, void* stream);
+
+/* Measurement aid for roofline reports: the rate at which this device streams `bytes` bytes (>= 16; the tail
+ * below a multiple of 16 is not read) of the device buffer `buf` (16-byte aligned, only read) through a
+ * read-only kernel whose threads keep eight 16-byte loads in flight, with plain loads (nontemporal == 0) or
+ * with the non-temporal hint the weight-streaming kernels use, in GB/s.  What a memory-bound kernel can
+ * reach lies below the published 8 TB/s; this is the reference the weight-streaming launches are held
+ * against.  Runs one warm-up launch and `launches` >= 1 timed ones on `stream` and waits for them.
+ * gb_per_s: host pointer.  Errors: MOE_ERR_INVALID_ARG, MOE_ERR_DEVICE. */
+moe_status moe_measure_hbm_read_rate(const void* buf /* device */, size_t bytes, int32_t nontemporal,
+                                     int32_t launches, float* gb_per_s /* host */, void* stream);
 
 /* Device pointer (into the workspace) to an int32 that the most recent moe_grouped_ffn / moe_layer_forward /
  * moe_profile_ffn call on this context set to 1 if it refused its offsets (offsets[E_local] above the host's

@@ -14,5 +14,6 @@ from .binding import (  # noqa: F401
     moe_gem_score,
     moe_gem_place,
     moe_measure_mfma_rate,
+    moe_measure_hbm_read_rate,
     moe_permute_noalloc,
 )

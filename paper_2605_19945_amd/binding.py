@@ -66,6 +66,7 @@ _SIGNATURES = {
     "moe_trace_mean_utilisation": (C.c_int, [_VP, _I32, _I32, _VP]),
     "moe_trace_correlation": (C.c_int, [_VP, _I32, _I32, _VP]),
     "moe_measure_mfma_rate": (C.c_int, [_I32, _I32, C.POINTER(C.c_float), _VP]),
+    "moe_measure_hbm_read_rate": (C.c_int, [_VP, C.c_size_t, _I32, _I32, C.POINTER(C.c_float), _VP]),
     "moe_ffn_refused_flag": (C.c_int, [_VP, C.POINTER(_VP)]),
     "moe_tile_rows": (_I32, [_VP]),
     "moe_set_tile_class": (C.c_int, [_VP, _I32]),
@@ -310,6 +311,18 @@ def moe_measure_mfma_rate(iters_per_wave=2500, launches=5):
     st = lib.moe_measure_mfma_rate(iters_per_wave, launches, C.byref(out), torch.cuda.current_stream().cuda_stream)
     if st != 0:
         raise MoEError(st, "moe_measure_mfma_rate")
+    return out.value
+
+
+def moe_measure_hbm_read_rate(buf, nontemporal=True, launches=10):
+    """GB/s at which a read-only kernel streams the device tensor `buf` (plain or non-temporal loads)."""
+    import torch
+    lib = load_library()
+    out = C.c_float()
+    st = lib.moe_measure_hbm_read_rate(buf.data_ptr(), buf.numel() * buf.element_size(), 1 if nontemporal else 0,
+                                       launches, C.byref(out), torch.cuda.current_stream().cuda_stream)
+    if st != 0:
+        raise MoEError(st, "moe_measure_hbm_read_rate")
     return out.value
 
 

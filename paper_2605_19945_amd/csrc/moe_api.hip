@@ -246,6 +246,31 @@ moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float
     return rc;
 }
 
+moe_status moe_measure_hbm_read_rate(const void* buf, size_t bytes, int32_t nontemporal, int32_t launches,
+                                     float* gb_per_s, void* stream) {
+    if (buf == nullptr || gb_per_s == nullptr || bytes < 16 || launches < 1 || !aligned(buf, 16))
+        return MOE_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (note_hip(hipEventCreate(&e0), "hipEventCreate") != MOE_OK) return MOE_ERR_DEVICE;
+    if (note_hip(hipEventCreate(&e1), "hipEventCreate") != MOE_OK) {
+        (void)hipEventDestroy(e0);
+        return MOE_ERR_DEVICE;
+    }
+    moe_status rc = note_hip(launch_read_rate(buf, bytes, nontemporal != 0, st), "read_rate_kernel");  // warm-up
+    if (rc == MOE_OK) rc = note_hip(hipEventRecord(e0, st), "hipEventRecord");
+    for (int i = 0; i < launches && rc == MOE_OK; ++i)
+        rc = note_hip(launch_read_rate(buf, bytes, nontemporal != 0, st), "read_rate_kernel");
+    if (rc == MOE_OK) rc = note_hip(hipEventRecord(e1, st), "hipEventRecord");
+    if (rc == MOE_OK) rc = note_hip(hipEventSynchronize(e1), "hipEventSynchronize");
+    float ms = 0.f;
+    if (rc == MOE_OK) rc = note_hip(hipEventElapsedTime(&ms, e0, e1), "hipEventElapsedTime");
+    if (rc == MOE_OK) *gb_per_s = ms > 0.f ? (float)((double)(bytes / 16 * 16) * launches / (ms * 1e6)) : 0.f;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
+
 moe_status moe_set_tile_class(moe_ctx* c, int32_t cls) {
     if (c == nullptr || cls < -1 || cls >= GEMM_NUM_CLASSES) return MOE_ERR_INVALID_ARG;
     c->forced_cls = cls;

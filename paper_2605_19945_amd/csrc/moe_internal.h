@@ -171,3 +171,5 @@ hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2
                         hipStream_t st);
 // one launch of the MFMA-only kernel (no loads); *flop: MFMA flop of the launch
 hipError_t launch_mfma_rate(int iters_per_wave, double* flop, hipStream_t st);
+// one launch of the read-only streaming kernel over bytes / 16 16-byte words of buf
+hipError_t launch_read_rate(const void* buf, size_t bytes, bool nontemporal, hipStream_t st);

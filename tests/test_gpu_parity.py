@@ -535,6 +535,23 @@ def test_sustained_mfma_rate_is_plausible(moe):
     assert 600.0 < rate < 2600.0
 
 
+def test_hbm_read_rate_is_plausible(moe):
+    """A read-only streaming kernel cannot exceed the published 8 TB/s and reaches a good part of it; a ragged
+    size (tail below 16 bytes, fewer words than threads) and a misaligned pointer are handled."""
+    import torch
+    buf = torch.empty(512 * 1024 * 1024 + 7, dtype=torch.uint8, device="cuda")
+    buf.random_(0, 255)
+    for nt in (False, True):
+        rate = moe.moe_measure_hbm_read_rate(buf, nontemporal=nt, launches=5)
+        print(f"   streaming read, non-temporal {nt}: {rate:.0f} GB/s", flush=True)
+        assert 2000.0 < rate < 8000.0
+    assert moe.moe_measure_hbm_read_rate(buf[:48], launches=1) > 0.0
+    with pytest.raises(moe.MoEError):
+        moe.moe_measure_hbm_read_rate(buf[1:4097])
+    with pytest.raises(moe.MoEError):
+        moe.moe_measure_hbm_read_rate(buf[:8])
+
+
 @pytest.mark.parametrize("which", ["resident_router", "gemm_router"])
 def test_layer_forward_under_graph_capture(moe, which):
     """moe_layer_forward records kernel launches only, so a caller may capture it into a HIP graph: every
