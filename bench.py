@@ -224,6 +224,13 @@ def run_gemm_trail(moe, ctx, s, cnt, packed, secs):
             rates.append(moe.moe_measure_mfma_rate(2500, 5))
     rows.append({"load": "MFMA only (v_mfma_f32_32x32x16_bf16, no loads)", "TFLOPs": sum(rates) / len(rates),
                  "sclk_MHz": cs.mean(), "ms": None})
+    with ClockSampler() as cs:
+        t0 = time.perf_counter()
+        rates = []
+        while time.perf_counter() - t0 < secs:
+            rates.append(moe.moe_measure_mfma_rate(2500, 5, shape=1))
+    rows.append({"load": "MFMA only (v_mfma_f32_16x16x32_bf16, no loads)", "TFLOPs": sum(rates) / len(rates),
+                 "sclk_MHz": cs.mean(), "ms": None})
     # (b) this library: both expert GEMMs on the workload's loads (rows already expert-contiguous)
     local = [int(c) for c in cnt[s.e_lo:s.e_lo + s.E_local]]
     A = sum(local)

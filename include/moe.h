@@ -27,7 +27,7 @@
  *   - The calls that take a stream only launch kernels on it (no memsets, no allocation, no host
  *     synchronisation), so they may be recorded under stream capture and replayed as a HIP graph; the
  *     exceptions are contexts created with MOE_FLAG_STAGE_EVENTS (they record events), moe_profile_ffn
- *     moe_measure_mfma_rate and moe_measure_hbm_read_rate (they time and wait).
+ *     moe_measure_mfma_rate(_of) and moe_measure_hbm_read_rate (they time and wait).
  */
 #ifndef MOE_H_
 #define MOE_H_
@@ -262,6 +262,11 @@ moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
  * `launches` >= 1 launches of iters_per_wave * 64 MFMAs per wavefront on `stream`, times them with events and waits for them.
  * tflops: host pointer.  Errors: MOE_ERR_INVALID_ARG, MOE_ERR_DEVICE. */
 moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops /* host */, void* stream);
+/* The same measurement on a chosen instruction shape: 0 = v_mfma_f32_32x32x16_bf16 (what the grouped GEMM
+ * issues; identical to moe_measure_mfma_rate), 1 = v_mfma_f32_16x16x32_bf16 (twice as many instructions for the
+ * same flop).  Under the power limit the sustained rate depends on the shape.  Errors as above. */
+moe_status moe_measure_mfma_rate_of(int32_t shape, int32_t iters_per_wave, int32_t launches,
+                                    float* tflops /* host */, void* stream);
 
 /* Measurement aid for roofline reports: the rate at which this device streams `bytes` bytes (>= 16; the tail
  * below a multiple of 16 is not read) of the device buffer `buf` (16-byte aligned, only read) through a

@@ -19,7 +19,9 @@ Pins (tests/test_oracle_pins.py): brute-force top-k with forced ties, gate-weigh
 count/permutation invariants and an O(T^2) literal stable-rank definition, a hand-derived worked
 example, identical experts == dense SwiGLU FFN evaluated by pure-Python loops and by a second
 library (torch fp64), one-hot inputs, W2 scaling, token-permutation equivariance and per-token
-independence.  No function here is unpinned.
+independence; the diagnostic bf16 rounding against hand-picked bit patterns and against an expert
+FFN whose intermediate is rebuilt by scalar loops; layer_forward under a given routing against the
+staged calls.  No function here is unpinned.
 """
 from __future__ import annotations
 

@@ -66,6 +66,7 @@ _SIGNATURES = {
     "moe_trace_mean_utilisation": (C.c_int, [_VP, _I32, _I32, _VP]),
     "moe_trace_correlation": (C.c_int, [_VP, _I32, _I32, _VP]),
     "moe_measure_mfma_rate": (C.c_int, [_I32, _I32, C.POINTER(C.c_float), _VP]),
+    "moe_measure_mfma_rate_of": (C.c_int, [_I32, _I32, _I32, C.POINTER(C.c_float), _VP]),
     "moe_measure_hbm_read_rate": (C.c_int, [_VP, C.c_size_t, _I32, _I32, C.POINTER(C.c_float), _VP]),
     "moe_ffn_refused_flag": (C.c_int, [_VP, C.POINTER(_VP)]),
     "moe_tile_rows": (_I32, [_VP]),
@@ -303,14 +304,16 @@ def _curve_arrays(curves):
     return counts, ms, off
 
 
-def moe_measure_mfma_rate(iters_per_wave=2500, launches=5):
-    """Sustained bf16 MFMA rate (TFLOP/s) of the current device under an MFMA-only load."""
+def moe_measure_mfma_rate(iters_per_wave=2500, launches=5, shape=0):
+    """Sustained bf16 MFMA rate (TFLOP/s) of the current device under an MFMA-only load; shape 0: 32x32x16
+    (the grouped GEMM's instruction), 1: 16x16x32."""
     import torch
     lib = load_library()
     out = C.c_float()
-    st = lib.moe_measure_mfma_rate(iters_per_wave, launches, C.byref(out), torch.cuda.current_stream().cuda_stream)
+    st = lib.moe_measure_mfma_rate_of(shape, iters_per_wave, launches, C.byref(out),
+                                      torch.cuda.current_stream().cuda_stream)
     if st != 0:
-        raise MoEError(st, "moe_measure_mfma_rate")
+        raise MoEError(st, "moe_measure_mfma_rate_of")
     return out.value
 
 

@@ -223,7 +223,12 @@ void moe_destroy(moe_ctx* c) {
 }
 
 moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops, void* stream) {
-    if (tflops == nullptr || iters_per_wave < 1 || launches < 1) return MOE_ERR_INVALID_ARG;
+    return moe_measure_mfma_rate_of(0, iters_per_wave, launches, tflops, stream);
+}
+
+moe_status moe_measure_mfma_rate_of(int32_t shape, int32_t iters_per_wave, int32_t launches, float* tflops,
+                                    void* stream) {
+    if (tflops == nullptr || iters_per_wave < 1 || launches < 1 || shape < 0 || shape > 1) return MOE_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (note_hip(hipEventCreate(&e0), "hipEventCreate") != MOE_OK) return MOE_ERR_DEVICE;
@@ -232,10 +237,10 @@ moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float
         return MOE_ERR_DEVICE;
     }
     double flop = 0;
-    moe_status rc = note_hip(launch_mfma_rate(iters_per_wave, &flop, st), "mfma_rate_kernel");  // warm-up
+    moe_status rc = note_hip(launch_mfma_rate(shape, iters_per_wave, &flop, st), "mfma_rate_kernel");  // warm-up
     if (rc == MOE_OK) rc = note_hip(hipEventRecord(e0, st), "hipEventRecord");
     for (int i = 0; i < launches && rc == MOE_OK; ++i)
-        rc = note_hip(launch_mfma_rate(iters_per_wave, &flop, st), "mfma_rate_kernel");
+        rc = note_hip(launch_mfma_rate(shape, iters_per_wave, &flop, st), "mfma_rate_kernel");
     if (rc == MOE_OK) rc = note_hip(hipEventRecord(e1, st), "hipEventRecord");
     if (rc == MOE_OK) rc = note_hip(hipEventSynchronize(e1), "hipEventSynchronize");
     float ms = 0.f;

@@ -275,6 +275,9 @@ hipError_t launch_router_gemm(const uint16_t* x, const uint16_t* rp, int T, int 
 // 0.5 .. 2) paired differently in every MFMA, so that the multipliers see changing inputs as they do in a
 // GEMM: with constant operands the same kernel runs at the full 2.4 GHz, with these it does not.
 __device__ float g_mfma_rate_sink;  // where the (never taken) store below goes: a real address
+// SHAPE 0: v_mfma_f32_32x32x16_bf16 (the grouped GEMM's instruction); SHAPE 1: v_mfma_f32_16x16x32_bf16 (half
+// the flop per instruction, a quarter of the accumulator registers: iters * 128 per wavefront for the same work).
+template <int SHAPE>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters) {
     const uint32_t lane = threadIdx.x & 63;
     bf16x8_t a[8], b[8];
@@ -289,21 +292,36 @@ __global__ __launch_bounds__(256) void mfma_rate_kernel(int iters) {
             h = h * 1664525u + 1013904223u;
             b[r][i] = __builtin_bit_cast(__bf16, (uint16_t)(((h >> 16) & 0x8000u) | ((126u + ((h >> 8) & 1u)) << 7) | ((h >> 20) & 0x7Fu)));
         }
-    f32x16_t acc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + u) & 7], acc[j], 0, 0, 0);
-    }
     float s = 0.f;
+    if constexpr (SHAPE == 0) {
+        f32x16_t acc[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) s += acc[j][j];
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + u) & 7], acc[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += acc[j][j];
+    } else {
+        f32x4_t acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int it = 0; it < 2 * iters; ++it) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j], b[(j + u) & 7], acc[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += acc[j][j & 3];
+    }
     if (s == 1.2345e-30f) g_mfma_rate_sink = s;  // practically never taken: keeps the sums live
 }
 
@@ -337,9 +355,10 @@ hipError_t launch_read_rate(const void* buf, size_t bytes, bool nontemporal, hip
     return hipGetLastError();
 }
 
-hipError_t launch_mfma_rate(int iters_per_wave, double* flop, hipStream_t st) {
+hipError_t launch_mfma_rate(int shape, int iters_per_wave, double* flop, hipStream_t st) {
     const int grid = SCHED_CU * 8;
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3(grid), dim3(256), 0, st, iters_per_wave);
+    if (shape == 0) hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(grid), dim3(256), 0, st, iters_per_wave);
+    else hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(grid), dim3(256), 0, st, iters_per_wave);
     *flop = (double)grid * 4 * (double)iters_per_wave * 64 * (2.0 * 32 * 32 * 16);
     return hipGetLastError();
 }

@@ -169,7 +169,8 @@ int gemm_pick_split2(const GemmPlan& p, int64_t n_rows, int E_local, int d, int 
 hipError_t launch_gemm2(const GemmPlan& p, const uint16_t* H, const uint16_t* W2f, int d, int f, uint16_t* Y,
                         const TileDesc* table, int nsplit, float* part, int64_t n_rows, const int32_t* n_rows_dev,
                         hipStream_t st);
-// one launch of the MFMA-only kernel (no loads); *flop: MFMA flop of the launch
-hipError_t launch_mfma_rate(int iters_per_wave, double* flop, hipStream_t st);
+// one launch of the MFMA-only kernel (no loads) on instruction shape 0 (32x32x16) or 1 (16x16x32); *flop: MFMA
+// flop of the launch (the same for both shapes)
+hipError_t launch_mfma_rate(int shape, int iters_per_wave, double* flop, hipStream_t st);
 // one launch of the read-only streaming kernel over bytes / 16 16-byte words of buf
 hipError_t launch_read_rate(const void* buf, size_t bytes, bool nontemporal, hipStream_t st);

@@ -530,9 +530,10 @@ def test_profile_ffn_runs_the_same_kernels_as_grouped_ffn(moe):
 def test_sustained_mfma_rate_is_plausible(moe):
     # an MFMA-only load cannot exceed the published dense bf16 peak and, on a healthy device, reaches a
     # good part of it
-    rate = moe.moe_measure_mfma_rate(300, 2)
-    print(f"   sustained MFMA-only rate {rate:.0f} TFLOP/s", flush=True)
-    assert 600.0 < rate < 2600.0
+    for shape in (0, 1):
+        rate = moe.moe_measure_mfma_rate(300, 2, shape=shape)
+        print(f"   sustained MFMA-only rate, shape {shape}: {rate:.0f} TFLOP/s", flush=True)
+        assert 600.0 < rate < 2600.0
 
 
 def test_hbm_read_rate_is_plausible(moe):

@@ -88,6 +88,7 @@ def test_create_and_call_validation_without_device(lib):
     assert lib.moe_set_tile_class(None, 0) == 1
     assert lib.moe_measure_mfma_rate(0, 1, None, None) == 1     # rejected before any device call
     assert lib.moe_measure_hbm_read_rate(None, 1024, 1, 1, None, None) == 1
+    assert lib.moe_measure_mfma_rate_of(2, 1, 1, None, None) == 1
     assert lib.moe_tile_rows(None) == 0
     lib.moe_destroy(None)                                                          # no-op
 
