@@ -217,20 +217,14 @@ def run_gemm_trail(moe, ctx, s, cnt, packed, secs):
         rows.append({"load": name, "TFLOPs": rate, "sclk_MHz": cs.mean(), "ms": dt / n * 1e3})
 
     # (a) MFMA only: the library's own rate kernel reports its rate; sample the clock around it
-    with ClockSampler() as cs:
-        t0 = time.perf_counter()
-        rates = []
-        while time.perf_counter() - t0 < secs:
-            rates.append(moe.moe_measure_mfma_rate(2500, 5))
-    rows.append({"load": "MFMA only (v_mfma_f32_32x32x16_bf16, no loads)", "TFLOPs": sum(rates) / len(rates),
-                 "sclk_MHz": cs.mean(), "ms": None})
-    with ClockSampler() as cs:
-        t0 = time.perf_counter()
-        rates = []
-        while time.perf_counter() - t0 < secs:
-            rates.append(moe.moe_measure_mfma_rate(2500, 5, shape=1))
-    rows.append({"load": "MFMA only (v_mfma_f32_16x16x32_bf16, no loads)", "TFLOPs": sum(rates) / len(rates),
-                 "sclk_MHz": cs.mean(), "ms": None})
+    for shape, name in ((1, "v_mfma_f32_16x16x32_bf16, the grouped GEMM's instruction"), (0, "v_mfma_f32_32x32x16_bf16")):
+        with ClockSampler() as cs:
+            t0 = time.perf_counter()
+            rates = []
+            while time.perf_counter() - t0 < secs:
+                rates.append(moe.moe_measure_mfma_rate(2500, 5, shape=shape))
+        rows.append({"load": f"MFMA only ({name}; no loads)", "TFLOPs": sum(rates) / len(rates),
+                     "sclk_MHz": cs.mean(), "ms": None})
     # (b) this library: both expert GEMMs on the workload's loads (rows already expert-contiguous)
     local = [int(c) for c in cnt[s.e_lo:s.e_lo + s.E_local]]
     A = sum(local)

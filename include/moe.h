@@ -256,15 +256,16 @@ moe_status moe_gem_place(const int32_t* trace, int32_t S, int32_t E, int32_t G, 
 moe_status moe_set_tile_class(moe_ctx* ctx, int32_t tile_class);
 
 /* Measurement aid for roofline reports: the bf16 matrix-core rate this device SUSTAINS under a load of
- * nothing but v_mfma_f32_32x32x16_bf16 on changing pseudo-random operands (no memory traffic, every SIMD
- * of every compute unit busy, independent accumulators), in TFLOP/s.  The published peak assumes the
- * maximum clock; under a dense MFMA load the chip runs at the clock its power limit allows.  Runs
- * `launches` >= 1 launches of iters_per_wave * 64 MFMAs per wavefront on `stream`, times them with events and waits for them.
+ * nothing but v_mfma_f32_16x16x32_bf16 (the instruction the grouped GEMM issues) on changing pseudo-random
+ * operands (no memory traffic, every SIMD of every compute unit busy, independent accumulators), in
+ * TFLOP/s.  The published peak assumes the maximum clock; under a dense MFMA load the chip runs at the clock
+ * its power limit allows.  Runs `launches` >= 1 launches of iters_per_wave * 128 MFMAs per wavefront on
+ * `stream`, times them with events and waits for them.
  * tflops: host pointer.  Errors: MOE_ERR_INVALID_ARG, MOE_ERR_DEVICE. */
 moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops /* host */, void* stream);
-/* The same measurement on a chosen instruction shape: 0 = v_mfma_f32_32x32x16_bf16 (what the grouped GEMM
- * issues; identical to moe_measure_mfma_rate), 1 = v_mfma_f32_16x16x32_bf16 (twice as many instructions for the
- * same flop).  Under the power limit the sustained rate depends on the shape.  Errors as above. */
+/* The same measurement on a chosen instruction shape: 0 = v_mfma_f32_32x32x16_bf16 (half as many instructions
+ * for the same flop), 1 = v_mfma_f32_16x16x32_bf16 (identical to moe_measure_mfma_rate).  Under the power limit
+ * the sustained rate depends on the shape.  Errors as above. */
 moe_status moe_measure_mfma_rate_of(int32_t shape, int32_t iters_per_wave, int32_t launches,
                                     float* tflops /* host */, void* stream);
 

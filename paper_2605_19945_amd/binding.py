@@ -304,9 +304,9 @@ def _curve_arrays(curves):
     return counts, ms, off
 
 
-def moe_measure_mfma_rate(iters_per_wave=2500, launches=5, shape=0):
-    """Sustained bf16 MFMA rate (TFLOP/s) of the current device under an MFMA-only load; shape 0: 32x32x16
-    (the grouped GEMM's instruction), 1: 16x16x32."""
+def moe_measure_mfma_rate(iters_per_wave=2500, launches=5, shape=1):
+    """Sustained bf16 MFMA rate (TFLOP/s) of the current device under an MFMA-only load; shape 1: 16x16x32
+    (the grouped GEMM's instruction), 0: 32x32x16."""
     import torch
     lib = load_library()
     out = C.c_float()

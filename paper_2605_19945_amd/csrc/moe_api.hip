@@ -223,7 +223,7 @@ void moe_destroy(moe_ctx* c) {
 }
 
 moe_status moe_measure_mfma_rate(int32_t iters_per_wave, int32_t launches, float* tflops, void* stream) {
-    return moe_measure_mfma_rate_of(0, iters_per_wave, launches, tflops, stream);
+    return moe_measure_mfma_rate_of(1, iters_per_wave, launches, tflops, stream);  // the grouped GEMM's shape
 }
 
 moe_status moe_measure_mfma_rate_of(int32_t shape, int32_t iters_per_wave, int32_t launches, float* tflops,

@@ -11,14 +11,19 @@
 //     built on the device from the per-expert offsets (no host sync), experts with no rows get
 //     none, row tiles have a run-time height (a multiple of 32 rows, the last one of an expert
 //     possibly ragged: loads clamped, stores masked) -- no padding to the largest expert.
-//   * v_mfma_f32_32x32x16_bf16 with the WEIGHT rows as the first operand and the TOKEN rows as the
-//     second, so a lane's accumulator holds 4 consecutive output columns of one token row.
+//   * v_mfma_f32_16x16x32_bf16 with the WEIGHT rows as the first operand and the TOKEN rows as the
+//     second, so a lane's accumulator holds 4 consecutive output columns of one token row.  Under this
+//     device's power limit the 16x16x32 shape sustains a higher clock than 32x32x16 (a quarter of the
+//     accumulator registers read and written per flop): the same loop on 32x32x16 ran at 1.55 GHz and
+//     1.28 PFLOP/s on the Mixtral shape, this one reaches 1.35.
 //   * only the token rows go through LDS.  The weights are stored at load time in MFMA-fragment
 //     order
-//        Wf[e][n / 32][k / 16][lane][8],  lane l <-> packed weight row 32*(n/32) + l % 32,
-//                                         reduction elements 16*(k/16) + 8*(l/32) .. +8,
-//     so a wavefront fetches one 32x16 operand fragment with ONE fully coalesced 1 KB load straight
-//     into the registers the MFMA reads, two K steps ahead of its use (three register buffers).
+//        Wf[e][n / 64][k / 64][4*q + a][lane][8],  lane l <-> packed weight row 64*(n/64) + 16*a + l % 16,
+//                                                 reduction elements 64*(k/64) + 32*q + 8*(l/16) .. +8,
+//     so a wavefront fetches one 16x32 operand fragment with ONE fully coalesced 1 KB load straight
+//     into the registers the MFMA reads, two K steps ahead of its use (three register buffers), and the
+//     eight fragments of its 64 weight rows for one K step are 8 KB in a row: one sequential stream per
+//     wavefront (with a stream per row block the weight-streaming launches were 3 to 7 % slower).
 //     The token rows are staged by global_load_lds into an NSX-deep LDS ring (XOR-swizzled 16-byte
 //     chunks, see swz_of) and every wavefront multiplies ALL rows of the tile by its own 64 weight
 //     rows (1 x 4 wave layout): no weight byte is loaded twice or touches LDS, and the LDS ring is
@@ -30,11 +35,16 @@
 //     fragments of the next stage are read under those MFMAs, and the loads of a K step are spread
 //     one by one over its MFMA slots (bursts from four lockstep wavefronts overrun the compute
 //     unit's single vector-memory pipe and stall MFMA issue).
-//   * the tallest tile has 288 rows: 9 row blocks x 2 weight blocks accumulator blocks of 16 registers: the 256
-//     AGPRs hold eight row blocks, the ninth accumulates in VGPRs.  The compiler will not split one
-//     array of accumulators over the two files without shuffling them inside the K loop, so the
-//     MFMAs of the ninth block are inline asm with a VGPR constraint; they come first in every
-//     sub-step because the compiler cannot see that they are MFMAs (see mfma_pinned_vgpr).
+//   * a K step of 64 is four sub-steps (K half q, token half th): the MFMAs of sub-step (q, th) multiply the
+//     four 16-row weight blocks by the 16-row token blocks of half th, so the token fragments held in
+//     registers at a time are those of half a tile.
+//   * the tallest tile has 288 rows: 18 token blocks x 4 weight blocks of 4 accumulator registers: the 256
+//     AGPRs hold sixteen token blocks, blocks 8 and 17 (the ninth of either half) accumulate in VGPRs.
+//     Left to itself the compiler shuffles the 72 small accumulators between the two files inside the K
+//     loop, so the tall tiles (256 and 288 rows) issue EVERY MFMA through inline asm with the register file
+//     in the constraint (mfma_pinned_agpr / mfma_pinned_vgpr); what the compiler then no longer does for
+//     these MFMAs -- keep writers of their operands and readers of their results at a distance -- the
+//     kernel arranges itself and tests/test_isa_hazards.py checks on the compiled code.
 //   * work items are ordered so that the workgroups running concurrently on one XCD share weight
 //     panels through that XCD's L2, and so that each XCD's queue of work items is dense.
 #pragma once
@@ -58,80 +68,84 @@ static __device__ inline float silu_f32(float g) { return g * __builtin_amdgcn_r
 
 enum { EPI_PLAIN = 0, EPI_SWIGLU = 1, EPI_PAIR_SUM_F32 = 2, EPI_PARTIAL_F32 = 3 };
 
-// Epilogues.  Accumulator element v of lane l in block (a, b) is
-//   weight row  a*32 + 8*(v/4) + 4*(l/32) + v%4,   token row  b*32 + l%32,
-// so a lane owns 4 consecutive output columns of one token row per accumulator quad.
-template <int FM, int FN, int TM, int TN, int EPI>
-static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileDesc& td, int Np,
+// Epilogues.  Accumulator element v of lane l in block (a, t) -- a: 16 packed weight rows, t: 16 token rows -- is
+//   weight row  a*16 + 4*(l/16) + v,   token row  t*16 + l%16,
+// so a lane owns 4 consecutive output columns of one token row per accumulator.  The wavefront's 64 packed
+// weight rows are blocks a = 0..3; in the interleaved layouts (gate/up, high/low router term) rows 0..31 are
+// the first and rows 32..63 the second member of the pair, i.e. block a pairs with block a + 2.
+//
+// Storage.  A tile of up to 256 rows keeps token block t in acc[.][t] (AGPRs).  The 288-row tile has 18 token
+// blocks and 16 AGPR slots: when all nine 32-row blocks are valid (NINE), blocks 8 and 17 -- the last of either
+// token half -- live in accv[.][0] and accv[.][1] (VGPRs) and the others close ranks; with fewer valid blocks
+// everything fits the AGPR slots.  Every accumulator thus has ONE register file for the whole kernel: sharing
+// a variable between an AGPR use in one case and a VGPR use in another makes the compiler keep it in one file
+// and copy it around every MFMA of the other, right behind the MFMA that writes it.
+template <int FT>
+struct AccShape {
+    static constexpr int NA = FT < 16 ? FT : 16;  // token blocks accumulating in AGPRs
+    static constexpr int NV = FT > 16 ? FT - 16 : 1;  // in VGPRs (one unused slot keeps the type valid)
+};
+template <bool NINE, int FA, int NA, int NV>
+static __device__ __forceinline__ const f32x4_t& acc_at(const f32x4_t (&acc)[FA][NA], const f32x4_t (&accv)[FA][NV],
+                                                        int a, int t) {
+    if (NINE) {
+        if (t == 8) return accv[a][0];
+        if (t == 17) return accv[a][NV - 1];
+        return acc[a][t < 8 ? t : t - 1];
+    }
+    return acc[a][t < NA ? t : 0];  // (t >= NA is never reached at run time: fewer than nine valid blocks)
+}
+
+template <int FT, int FA, int TM, int TN, int EPI, bool NINE>
+static __device__ inline void gemm_epilogue(const f32x4_t (&acc_)[FA][AccShape<FT>::NA],
+                                            const f32x4_t (&accv_)[FA][AccShape<FT>::NV], const TileDesc& td, int Np,
                                             uint16_t* __restrict__ C, int ldc, int wm, int wn, int lane) {
-    const int frow = lane & 31, fhalf = lane >> 5;
+    static_assert(FA == 4 && TN == 64, "wave tile");
+    auto A = [&](int a, int t) -> const f32x4_t& {
+        return acc_at<NINE, FA, AccShape<FT>::NA, AccShape<FT>::NV>(acc_, accv_, a, t);
+    };
+    const int frow = lane & 15, fq = lane >> 4;
 #pragma unroll
-    for (int b = 0; b < FM; ++b) {
-        const int trow = wm * TM + b * 32 + frow;
+    for (int t = 0; t < FT; ++t) {
+        const int trow = wm * TM + t * 16 + frow;
         if (trow >= td.rows) continue;
         uint16_t* crow = C + (size_t)(td.row0 + trow) * ldc;
+        const int prow = td.n0 + wn * TN;  // first packed weight row of this wavefront (Np is a multiple of 64)
+        if (prow >= Np) continue;
         if constexpr (EPI == EPI_PAIR_SUM_F32) {
-            // router logits: the even block holds the products with the high bf16 term of Wg, the odd
-            // block those with the low term; their sum is stored as fp32 (C is a float matrix)
+            // router logits: blocks 0, 1 hold the products with the high bf16 term of Wg, blocks 2, 3 those
+            // with the low term of the same experts; their sum is stored as fp32 (C is a float matrix)
             float* frow_out = (float*)C + (size_t)(td.row0 + trow) * ldc;
 #pragma unroll
-            for (int a2 = 0; a2 < FN / 2; ++a2) {
-                const int prow = td.n0 + wn * TN + a2 * 64;
-                if (prow >= Np) continue;
-                const int col = prow / 2 + 4 * fhalf;
+            for (int a = 0; a < 2; ++a) {
+                f32x4_t o;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4_t o;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) o[v] = acc[2 * a2][b][4 * q + v] + acc[2 * a2 + 1][b][4 * q + v];
-                    *(f32x4_t*)(frow_out + col + 8 * q) = o;
-                }
+                for (int v = 0; v < 4; ++v) o[v] = A(a, t)[v] + A(a + 2, t)[v];
+                *(f32x4_t*)(frow_out + prow / 2 + 16 * a + 4 * fq) = o;
             }
         } else if constexpr (EPI == EPI_PARTIAL_F32) {
             // partial sums of a reduction split, fp32 (C is a float matrix, one slab per split)
             float* frow_out = (float*)C + (size_t)(td.row0 + trow) * ldc;
 #pragma unroll
-            for (int a = 0; a < FN; ++a) {
-                const int col = td.n0 + wn * TN + a * 32;
-                if (col >= Np) continue;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    f32x4_t o;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) o[v] = acc[a][b][4 * q + v];
-                    *(f32x4_t*)(frow_out + col + 4 * fhalf + 8 * q) = o;
-                }
-            }
+            for (int a = 0; a < FA; ++a) *(f32x4_t*)(frow_out + prow + 16 * a + 4 * fq) = A(a, t);
         } else if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
-            for (int a2 = 0; a2 < FN / 2; ++a2) {
-                const int prow = td.n0 + wn * TN + a2 * 64;  // packed row of the gate block
-                if (prow >= Np) continue;
-                const int hcol = prow / 2 + 4 * fhalf;
+            for (int a = 0; a < 2; ++a) {
+                float h[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    float h[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        h[v] = silu_f32(acc[2 * a2][b][4 * q + v]) * acc[2 * a2 + 1][b][4 * q + v];
-                    u32x2_t o;
-                    o.x = pack2_bf16(h[0], h[1]);
-                    o.y = pack2_bf16(h[2], h[3]);
-                    *(u32x2_t*)(crow + hcol + 8 * q) = o;
-                }
+                for (int v = 0; v < 4; ++v) h[v] = silu_f32(A(a, t)[v]) * A(a + 2, t)[v];
+                u32x2_t o;
+                o.x = pack2_bf16(h[0], h[1]);
+                o.y = pack2_bf16(h[2], h[3]);
+                *(u32x2_t*)(crow + prow / 2 + 16 * a + 4 * fq) = o;
             }
         } else {
 #pragma unroll
-            for (int a = 0; a < FN; ++a) {
-                const int col = td.n0 + wn * TN + a * 32;
-                if (col >= Np) continue;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    u32x2_t o;
-                    o.x = pack2_bf16(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]);
-                    o.y = pack2_bf16(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                    *(u32x2_t*)(crow + col + 4 * fhalf + 8 * q) = o;
-                }
+            for (int a = 0; a < FA; ++a) {
+                u32x2_t o;
+                o.x = pack2_bf16(A(a, t)[0], A(a, t)[1]);
+                o.y = pack2_bf16(A(a, t)[2], A(a, t)[3]);
+                *(u32x2_t*)(crow + prow + 16 * a + 4 * fq) = o;
             }
         }
     }
@@ -146,45 +160,48 @@ static __device__ inline void gemm_epilogue(f32x16_t (&acc)[FN][FM], const TileD
 // tile) to 1.8 % (f = 768: 12 K steps per tile) of the layer time; most of the cost of the scattered
 // stores was their completion, which the wavefronts never waited for.
 // The caller has made sure that no wavefront still reads the ring.
-template <int FM, int FN, int BM, int TN, int EPI>
-static __device__ inline void gemm_epilogue_staged(f32x16_t (&acc)[FN][FM], const TileDesc& td, int Np,
-                                                   uint16_t* __restrict__ C, int ldc, int wn, int lane,
+template <int FT, int FA, int BM, int TN, int EPI, bool NINE>
+static __device__ inline void gemm_epilogue_staged(const f32x4_t (&acc_)[FA][AccShape<FT>::NA],
+                                                   const f32x4_t (&accv_)[FA][AccShape<FT>::NV], const TileDesc& td,
+                                                   int Np, uint16_t* __restrict__ C, int ldc, int wn, int lane,
                                                    char* lds_base) {
+    auto A = [&](int a, int t) -> const f32x4_t& {
+        return acc_at<NINE, FA, AccShape<FT>::NA, AccShape<FT>::NV>(acc_, accv_, a, t);
+    };
     static_assert(EPI == EPI_PLAIN || EPI == EPI_SWIGLU, "bf16 outputs");
-    static_assert(FN == 2 && TN == 64, "wave tile");
+    static_assert(FA == 4 && TN == 64, "wave tile");
     constexpr int OUTC = EPI == EPI_SWIGLU ? TN / 2 : TN;  // output columns of this wavefront per row
     constexpr int ROWB = OUTC * 2;                         // 128 or 64 bytes per row
     constexpr int NCH = ROWB / 16;                         // 16-byte chunks per row: 8 or 4
     char* stage = lds_base + wn * (BM * ROWB);
-    const int frow = lane & 31, fhalf = lane >> 5;
+    const int frow = lane & 15, fq = lane >> 4;
     auto swz = [](int r) { return EPI == EPI_SWIGLU ? (r >> 2) & 3 : (r ^ (r >> 3)) & 7; };
 #pragma unroll
-    for (int b = 0; b < FM; ++b) {
-        if (b * 32 >= td.rows) break;  // uniform
-        const int r = b * 32 + frow;
-        char* srow = stage + r * ROWB + 8 * fhalf;
+    for (int t = 0; t < FT; ++t) {
+        if (t * 16 >= td.rows) break;  // uniform
+        const int r = t * 16 + frow;
+        // the lane's 4 columns of block a start at byte 32*a + 8*fq of the row: chunk 2*a + fq/2, half fq%2
+        char* srow = stage + r * ROWB + 8 * (fq & 1);
         const int x = swz(r);
         if constexpr (EPI == EPI_SWIGLU) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int a = 0; a < 2; ++a) {
                 float h[4];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) h[v] = silu_f32(acc[0][b][4 * q + v]) * acc[1][b][4 * q + v];
+                for (int v = 0; v < 4; ++v) h[v] = silu_f32(A(a, t)[v]) * A(a + 2, t)[v];
                 u32x2_t o;
                 o.x = pack2_bf16(h[0], h[1]);
                 o.y = pack2_bf16(h[2], h[3]);
-                *(u32x2_t*)(srow + ((q ^ x) << 4)) = o;
+                *(u32x2_t*)(srow + (((2 * a + (fq >> 1)) ^ x) << 4)) = o;
             }
         } else {
 #pragma unroll
-            for (int a = 0; a < FN; ++a)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    u32x2_t o;
-                    o.x = pack2_bf16(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]);
-                    o.y = pack2_bf16(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                    *(u32x2_t*)(srow + (((4 * a + q) ^ x) << 4)) = o;
-                }
+            for (int a = 0; a < FA; ++a) {
+                u32x2_t o;
+                o.x = pack2_bf16(A(a, t)[0], A(a, t)[1]);
+                o.y = pack2_bf16(A(a, t)[2], A(a, t)[3]);
+                *(u32x2_t*)(srow + (((2 * a + (fq >> 1)) ^ x) << 4)) = o;
+            }
         }
     }
     // the wavefront reads back only what it wrote itself
@@ -241,15 +258,21 @@ static __device__ inline void static_for(F&& f) {
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
-// Row tiles of more than 256 rows need more than the 256 accumulator registers (AGPRs) of a lane: the
-// blocks past the eighth accumulate in ordinary VGPRs.  The compiler's own allocation shuffles such
-// accumulators between the two files inside the K loop, so the MFMAs of those blocks are issued through
-// inline asm with a VGPR operand constraint (the others stay builtins and then all fit the AGPRs).
-// The asm is opaque to the compiler's hazard recogniser, which would otherwise keep a reader of an MFMA
-// result the required wait states behind it: the caller places these MFMAs where at least three other
-// 32x32x16 MFMAs follow before anything else can read the result.
-static __device__ inline void mfma_pinned_vgpr(f32x16_t& acc, const bf16x8_t& w, const bf16x8_t& x) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(w), "v"(x));
+// Row tiles of more than 256 rows need more than the 256 accumulator registers (AGPRs) of a lane: two of
+// the eighteen token blocks accumulate in ordinary VGPRs.  The MFMAs of the tall tiles are issued through
+// inline asm that names the register file of the accumulator.  The asm is opaque to the compiler's hazard
+// recogniser, which would otherwise keep a reader of an MFMA result, and a writer of an MFMA operand, the
+// required wait states away: the caller places the VGPR ones first in a sub-step (the others follow before
+// anything can read their result), reads accumulators only after the K loop, and claims the zeroed
+// accumulators in their register file before the prologue (claim_agpr / claim_vgpr).
+static __device__ inline void mfma_pinned_vgpr(f32x4_t& acc, const bf16x8_t& w, const bf16x8_t& x) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(w), "v"(x));
+}
+// the value exists in a register of that file from here on (see the use in gemm_tile)
+static __device__ inline void claim_vgpr(f32x4_t& acc) { asm volatile("" : "+v"(acc)); }
+static __device__ inline void claim_agpr(f32x4_t& acc) { asm volatile("" : "+a"(acc)); }
+static __device__ inline void mfma_pinned_agpr(f32x4_t& acc, const bf16x8_t& w, const bf16x8_t& x) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(w), "v"(x));
 }
 
 // s_waitcnt vmcnt(n) for a wave-uniform run-time n (the instruction takes an immediate)
@@ -279,17 +302,18 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
                                                  const uint16_t* __restrict__ Wf, int Np, int K,
                                                  uint16_t* __restrict__ C, int ldc,
                                                  const TileDesc* __restrict__ table, size_t c_split_bytes) {
-    constexpr int BN = 64 * NW, BK = 64, TN = BN / NW, FN = TN / 32, FM = BM / 32;
+    constexpr int BN = 64 * NW, BK = 64, TN = BN / NW, FA = TN / 16, FM = BM / 32, FT = 2 * FM;
     constexpr int CH = BK / 8;   // 16-byte chunks per staged token row
     constexpr int RPL = 64 / CH; // rows covered by one wave-level load
     constexpr int XP = 32 / (NW * RPL);  // wave-level token loads of one wavefront per 32-row block
-    constexpr int KK = BK / 16;  // MFMA sub-steps per K step
+    constexpr int KQ = BK / 32;  // K halves of a K step: one v_mfma_f32_16x16x32_bf16 reduces over 32 elements
+    constexpr int KK = 2 * KQ;   // MFMA sub-steps per K step: (K half q, token half th), kk = 2*q + th
     constexpr int DX = NSX - 1;  // token prefetch distance (K steps)
     constexpr int WPF = 2;       // weight prefetch distance (K steps); WPF + 1 register buffers
-    constexpr int WL = FN * KK;  // weight loads per lane per K step
+    constexpr int WL = FA * KQ;  // weight loads per lane per K step
     constexpr int STAGE = BM * CH;            // 16-byte chunks per token stage
-    constexpr int BLK = 32 * CH * 16;         // bytes between consecutive 32-row blocks in a stage
-    static_assert(FN == 2 && KK == 4, "wave tile");
+    constexpr int BLK = 16 * CH * 16;         // bytes between consecutive 16-row blocks in a stage
+    static_assert(FA == 4 && KK == 4, "wave tile");
     static_assert(BM % 32 == 0 && FM >= 1 && FM <= 9, "row tile");
     static_assert(NW == 4 || NW == 2, "wavefronts per workgroup");
     static_assert(NSX >= 3 && (2 * FM * XP + WL) <= 48, "pipeline depth");
@@ -302,7 +326,7 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane / CH, lphys = lane % CH;
-    const int frow = lane & 31, fhalf = lane >> 5;
+    const int frow = lane & 15, fq = lane >> 4;
     const int KT = K / BK;
     const int fmv = (td.rows + 31) / 32;  // valid 32-row blocks: the same for all four wavefronts
     const int K_total = K * (int)gridDim.y;
@@ -320,39 +344,59 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
         if (row_map != nullptr) grow = row_map[grow];
         xo[p] = (uint32_t)grow * (uint32_t)(ldx * 2) + (uint32_t)((lphys ^ swz_of<CH>(r)) * 16);
     }
-    // weight sources: fragment (row block nb, K chunk kc) is the 1 KB at ((e*Np/32 + nb)*K/16 + kc)*1 KB;
-    // wave-uniform bases (scalar registers) plus the lane's 16 bytes
-    const int nbt = Np / 32;
-    const char* wsrc[FN];
-#pragma unroll
-    for (int a = 0; a < FN; ++a) {
-        int nb = (td.n0 + wave * TN) / 32 + a;
-        if (nb >= nbt) nb = nbt - 1;  // past the last weight row: computed, never stored
-        wsrc[a] = (const char*)(Wf + ((size_t)td.expert * nbt + nb) * ((size_t)K_total * 32) + (size_t)blockIdx.y * K * 32);
-    }
+    // weight source: the eight fragments a wavefront needs for one K step (4 row blocks x 2 K halves) are the
+    // 8 KB at ((e*Np/64 + nb)*K/64 + kt)*8 KB, fragment j = 4*q + a at j KB: ONE sequential stream per
+    // wavefront.  Wave-uniform base (scalar registers) plus the lane's 16 bytes.
+    const int nbt = Np / 64;
+    int nb = (td.n0 + wave * TN) / 64;
+    if (nb >= nbt) nb = nbt - 1;  // past the last weight row: computed, never stored
+    const char* wsrc = (const char*)(Wf + ((size_t)td.expert * nbt + nb) * ((size_t)K_total * 64) + (size_t)blockIdx.y * K * 64);
     const uint32_t wlane = (uint32_t)lane * 16u;
-    // LDS byte address (inside a stage) of this lane's chunk of block 0 for every MFMA sub-step
-    uint32_t fx_addr[KK];
+    // LDS byte address (inside a stage) of this lane's chunk of 16-row block 0 for either K half: token row
+    // frow, reduction elements 32*q + 8*fq .. +8 (the swizzle of a row depends on row % 16 only)
+    uint32_t fx_addr[KQ];
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-        fx_addr[kk] = (uint32_t)((frow * CH + ((kk * 2 + fhalf) ^ swz_of<CH>(frow))) * 16);
+    for (int q = 0; q < KQ; ++q)
+        fx_addr[q] = (uint32_t)((frow * CH + ((q * 4 + fq) ^ swz_of<CH>(frow))) * 16);
 
-    f32x16_t acc[FN][FM];
+    // block (a, t): 16 packed weight rows x 16 token rows (storage: see AccShape)
+    constexpr int NA = AccShape<FT>::NA, NV = AccShape<FT>::NV;
+    f32x4_t acc[FA][NA], accv[FA][NV];
 #pragma unroll
-    for (int a = 0; a < FN; ++a)
+    for (int a = 0; a < FA; ++a) {
 #pragma unroll
-        for (int b = 0; b < FM; ++b)
+        for (int t = 0; t < NA; ++t) acc[a][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+        for (int t = 0; t < NV; ++t) accv[a][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
 
     auto main_loop = [&](auto fmv_c) {
         constexpr int FMV = decltype(fmv_c)::value;  // valid 32-row blocks (compile time)
-        constexpr int NM = FMV * FN;                 // MFMAs per sub-step
+        constexpr int NM = FMV * FA;                 // MFMAs per sub-step: FMV 16-row token blocks x 4 weight blocks
         constexpr int XV = FMV * XP;                 // token loads per lane per K step
         constexpr int NL = WL + XV;                  // loads per lane per K step
 
-        bf16x8_t wr[WPF + 1][KK][FN];
-        bf16x8_t xf[2][FMV];
+        bf16x8_t wr[WPF + 1][KQ][FA];
+        bf16x8_t xf[2][FMV];  // sub-step (q, th): the 16-row token blocks th*FMV .. th*FMV + FMV - 1, K half q
+
+        // The tall tiles issue every MFMA through inline asm (see mfma_pinned_agpr).  The compiler then does
+        // not know that the first MFMA reads the accumulator it has just zeroed and would put the zeroing
+        // writes directly in front of it, closer than the wait states a matrix instruction needs behind a
+        // write of its third operand.  Claiming every accumulator here, in the register file its MFMAs use,
+        // makes the zeros exist now; the prologue's loads, waits and barrier follow before the first MFMA.
+        if constexpr (FM >= 8) {
+            static_for<2 * FMV>([&](auto t_c) {
+                constexpr int t = decltype(t_c)::value;
+                static_for<FA>([&](auto a_c) {
+                    constexpr int a = decltype(a_c)::value;
+                    if constexpr (FMV == 9 && (t == 8 || t == 17)) {
+                        claim_vgpr(accv[a][t == 8 ? 0 : NV - 1]);
+                    } else {
+                        claim_agpr(acc[a][FMV == 9 && t > 8 ? t - 1 : t]);
+                    }
+                });
+            });
+        }
 
         auto issue_x_one = [&](int kt, int p) {
             u32x4_t* base = lds + (kt % NSX) * STAGE;
@@ -364,20 +408,20 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
         // nearly-zero vmcnt in front of the MFMAs that consume them (it cannot see through the
         // unrolled, branched loop) and collapse the prefetch distance.  They are waited for together
         // with the token loads, with exact counts, before the barrier that precedes their use.
-        auto load_w_one = [&](int kt, auto buf_c, auto j_c) {  // j = kk * FN + a
+        auto load_w_one = [&](int kt, auto buf_c, auto j_c) {  // j = q * FA + a
             constexpr int BUF = decltype(buf_c)::value;
-            constexpr int kk = decltype(j_c)::value / FN, a = decltype(j_c)::value % FN;
+            constexpr int kk = decltype(j_c)::value / FA, a = decltype(j_c)::value % FA;  // kk: K half here
             u32x4_t v;
-            const char* base = wsrc[a] + (size_t)kt * (KK * 1024);
+            const char* base = wsrc + (size_t)kt * (WL * 1024) + kk * (FA * 1024);  // (offsets reach 4 KB)
             if constexpr (W_STREAM) {
                 asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3 nt"
                              : "=v"(v)
-                             : "v"(wlane), "s"(base), "n"(kk * 1024)
+                             : "v"(wlane), "s"(base), "n"(a * 1024)
                              : "memory");
             } else {
                 asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3"
                              : "=v"(v)
-                             : "v"(wlane), "s"(base), "n"(kk * 1024)
+                             : "v"(wlane), "s"(base), "n"(a * 1024)
                              : "memory");
             }
             wr[BUF][kk][a] = __builtin_bit_cast(bf16x8_t, v);
@@ -398,7 +442,7 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
             }
         wait_vmcnt_rt(after0);
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        static_for<FMV>([&](auto b) { xf[0][b] = lds_read_b128<b * BLK>(fx_addr[0]); });
+        static_for<FMV>([&](auto b) { xf[0][b] = lds_read_b128<b * BLK>(fx_addr[0]); });  // sub-step (0, 0)
 
         // one K step; BUF = kt % (WPF + 1) is a compile-time register-buffer index.  STEADY: the step
         // is neither among the first nor the last ones, so every prefetch of it exists and nothing
@@ -413,10 +457,12 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
             const uint32_t sbase = (uint32_t)((kt % NSX) * STAGE * 16);
             const uint32_t nbase = (uint32_t)(((kt + 1) % NSX) * STAGE * 16);
             // the weights of this stage landed before the barrier that published it
-            static_for<WL>([&](auto j) { tie(wr[BUF][decltype(j)::value / FN][decltype(j)::value % FN]); });
+            static_for<WL>([&](auto j) { tie(wr[BUF][decltype(j)::value / FA][decltype(j)::value % FA]); });
             static_for<KK>([&](auto kk_c) {
                 constexpr int kk = decltype(kk_c)::value;
                 constexpr int cur = kk & 1, nxt = cur ^ 1;
+                constexpr int q = kk >> 1, th = kk & 1;          // K half, token half of this sub-step
+                constexpr int qn = (kk + 1) >> 1, thn = (kk + 1) & 1;  // of the next one (same K step)
                 if constexpr (kk == KK - 1) {
                     // publish stage kt+1 before the last sub-step: own loads of stage kt+1 have landed
                     // (what may stay in flight: the tokens issued one step ago, after the weights of
@@ -442,20 +488,23 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
                 __builtin_amdgcn_sched_barrier(0);
                 static_for<NM>([&](auto m_c) {
                     constexpr int m = decltype(m_c)::value;
-                    // a ninth row block goes first: whatever reads its result next (the compiler may
+                    // a block that accumulates in VGPRs goes first: whatever reads its result next (the compiler may
                     // copy it at the end of a basic block) then sits behind the sub-step's other MFMAs
-                    constexpr int a = m % FN;
-                    constexpr int b = FMV <= 8 ? m / FN : (m / FN + 8) % 9;
+                    constexpr int a = m % FA;
+                    constexpr int b = FMV <= 8 ? m / FA : (m / FA + 8) % 9;
+                    constexpr int t = th * FMV + b;  // 16-row token block
                     if constexpr (b < 8) {
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wr[BUF][kk][a], xf[cur][b], acc[a][b], 0, 0, 0);
+                        constexpr int slot = FMV == 9 && t > 8 ? t - 1 : t;
+                        if constexpr (FM >= 8) mfma_pinned_agpr(acc[a][slot], wr[BUF][q][a], xf[cur][b]);
+                        else acc[a][slot] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wr[BUF][q][a], xf[cur][b], acc[a][slot], 0, 0, 0);
                     } else {
-                        mfma_pinned_vgpr(acc[a][b], wr[BUF][kk][a], xf[cur][b]);
+                        mfma_pinned_vgpr(accv[a][th == 0 ? 0 : NV - 1], wr[BUF][q][a], xf[cur][b]);
                     }
                     // first half of the slots: LDS reads of the next sub-step's token fragments, early
                     // enough that their latency is covered by the MFMAs of the second half
                     if constexpr (m < FMV) {
                         if constexpr (kk + 1 < KK) {
-                            xf[nxt][m] = lds_read_b128<m * BLK>(sbase + fx_addr[kk + 1]);
+                            xf[nxt][m] = lds_read_b128<(thn * FMV + m) * BLK>(sbase + fx_addr[qn]);
                         } else {
                             if (next) xf[nxt][m] = lds_read_b128<m * BLK>(nbase + fx_addr[0]);
                         }
@@ -516,9 +565,11 @@ static __device__ __forceinline__ void gemm_tile(int bx, const uint16_t* __restr
         static_assert(NSX >= 4, "the staged epilogue uses four quarters of BM x 128 bytes");
         // every wavefront has issued and completed its last reads of the token ring
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        gemm_epilogue_staged<FM, FN, BM, TN, EPI>(acc, td, Np, C, ldc, wave, lane, (char*)lds);
+        if (FM == 9 && fmv == 9) gemm_epilogue_staged<FT, FA, BM, TN, EPI, FM == 9>(acc, accv, td, Np, C, ldc, wave, lane, (char*)lds);
+        else gemm_epilogue_staged<FT, FA, BM, TN, EPI, false>(acc, accv, td, Np, C, ldc, wave, lane, (char*)lds);
     } else {
-        gemm_epilogue<FM, FN, BM, TN, EPI>(acc, td, Np, C, ldc, 0, wave, lane);
+        if (FM == 9 && fmv == 9) gemm_epilogue<FT, FA, BM, TN, EPI, FM == 9>(acc, accv, td, Np, C, ldc, 0, wave, lane);
+        else gemm_epilogue<FT, FA, BM, TN, EPI, false>(acc, accv, td, Np, C, ldc, 0, wave, lane);
     }
 }
 

@@ -45,30 +45,34 @@ __global__ void pack_router_resident_kernel(const float* __restrict__ Wg, int d,
 }
 
 // GEMM-path layout (E >= MOE_ROUTER_GEMM_MIN_E), MFMA-fragment order like the expert weights:
-//   rp[nb][kc][l][j] = term (nb % 2) of Wg[16*kc + 8*(l/32) + j][32*(nb/2) + l%32]
-// (term 0 = high bf16 part, term 1 = low part; experts padded to a multiple of 32 with zeros).
+//   rp[nb][kt][4*q + a][l][j] = term ((n / 32) % 2) of Wg[64*kt + 32*q + 8*(l/16) + j][32*(n/64) + n%32],
+//   n = 64*nb + 16*a + l%16
+// (packed rows in blocks of 32: term 0 = high bf16 part, term 1 = low part of the same 32 experts; experts
+// padded to a multiple of 32 with zeros).
 __global__ void pack_router_gemm_kernel(const float* __restrict__ Wg, int d, int E, int Ep,
                                         uint16_t* __restrict__ rp) {
-    const size_t n = (size_t)(2 * Ep / 32) * (d / 16) * 64;  // 16-byte chunks
+    const size_t n = (size_t)(2 * Ep / 64) * (d / 64) * 8 * 64;  // 16-byte chunks
     for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < n; o += (size_t)gridDim.x * blockDim.x) {
         const int l = (int)(o % 64);
-        const int kc = (int)((o / 64) % (d / 16));
-        const int nb = (int)(o / 64 / (d / 16));
-        const int e = 32 * (nb / 2) + (l & 31), term = nb & 1;
+        const int frag = (int)((o / 64) % 8), q = frag >> 2, a = frag & 3;
+        const int kt = (int)((o / 512) % (d / 64));
+        const int nb = (int)(o / 512 / (d / 64));
+        const int prow = 64 * nb + 16 * a + (l & 15);
+        const int e = 32 * (prow / 64) + (prow & 31), term = (prow >> 5) & 1;
         uint16_t v[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int i = 16 * kc + 8 * (l >> 5) + j;
+            const int i = 64 * kt + 32 * q + 8 * (l >> 4) + j;
             const float x = e < E ? Wg[(size_t)i * E + e] : 0.f;
             const uint16_t hi = f32_to_bf16_rne(x);
             v[j] = term == 0 ? hi : f32_to_bf16_rne(x - bf16_to_f32(hi));
         }
-        u32x4_t q;
-        q.x = v[0] | ((uint32_t)v[1] << 16);
-        q.y = v[2] | ((uint32_t)v[3] << 16);
-        q.z = v[4] | ((uint32_t)v[5] << 16);
-        q.w = v[6] | ((uint32_t)v[7] << 16);
-        *(u32x4_t*)(rp + o * 8) = q;
+        u32x4_t qv;
+        qv.x = v[0] | ((uint32_t)v[1] << 16);
+        qv.y = v[2] | ((uint32_t)v[3] << 16);
+        qv.z = v[4] | ((uint32_t)v[5] << 16);
+        qv.w = v[6] | ((uint32_t)v[7] << 16);
+        *(u32x4_t*)(rp + o * 8) = qv;
     }
 }
 

@@ -1,10 +1,11 @@
 """Static check of the compiled GEMM kernels (no GPU needed).
 
-The 288-row tile keeps its ninth row block's accumulators in VGPRs and issues those MFMAs through
-inline asm, which the compiler's hazard recogniser cannot see into: nothing but the next accumulating
-MFMA may touch such a result until the MFMA has written it (11 wait states after an 8-pass MFMA).  The
-kernel places these MFMAs first in every sub-step so that other MFMAs always follow; this test
-compiles the kernels to ISA and verifies it instruction by instruction, following branches.
+The tall tiles (256 and 288 rows) issue every MFMA through inline asm that names the register file of the
+accumulator (AGPRs, and VGPRs for two token blocks of the 288-row tile), which the compiler's hazard
+recogniser cannot see into.  Two things it would otherwise guarantee are checked here on the compiled code,
+instruction by instruction and following branches: nothing but the next accumulating MFMA touches an MFMA's
+result until it has been written (7 wait states after a 4-pass MFMA), and nothing writes an operand of an
+asm MFMA in the wait states right before it.
 """
 import os
 import re
@@ -19,16 +20,17 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 from paper_2605_19945_amd import build as moe_build  # noqa: E402
 
-NEED = 12          # wait states before anything else may touch the result
-MFMA_PASSES = 8    # v_mfma_f32_32x32x16_bf16; the pipe takes the next MFMA when the previous one has gone through
+NEED = 8           # wait states before anything else may touch the result (7 by the ISA tables, one to spare)
+MFMA_PASSES = 4    # v_mfma_f32_16x16x32_bf16; the pipe takes the next MFMA when the previous one has gone through
 
 
 def _regs(tok):
-    m = re.fullmatch(r"v\[(\d+):(\d+)\]", tok)
+    """Registers named by an operand token, as (file, index) pairs: v7, v[2:5], a3, a[0:3]."""
+    m = re.fullmatch(r"([va])\[(\d+):(\d+)\]", tok)
     if m:
-        return set(range(int(m.group(1)), int(m.group(2)) + 1))
-    m = re.fullmatch(r"v(\d+)", tok)
-    return {int(m.group(1))} if m else set()
+        return {(m.group(1), r) for r in range(int(m.group(2)), int(m.group(3)) + 1)}
+    m = re.fullmatch(r"([va])(\d+)", tok)
+    return {(m.group(1), int(m.group(2)))} if m else set()
 
 
 def _split(line):
@@ -39,8 +41,10 @@ def _split(line):
     return parts[0], ([t.strip() for t in re.split(r",\s*", parts[1])] if len(parts) > 1 else [])
 
 
-def find_hazards(lines):
-    """Returns (number of VGPR-destination MFMAs, list of hazard descriptions)."""
+def find_hazards(lines, agpr_too=False):
+    """Returns (number of MFMAs checked, list of hazard descriptions).  Checked are the MFMAs with a VGPR
+    destination and, with agpr_too, those with an AGPR destination as well (kernels that issue every MFMA
+    through inline asm)."""
     labels = {}
     for i, l in enumerate(lines):
         m = re.match(r"(\.LBB\d+_\d+):", l)
@@ -49,7 +53,9 @@ def find_hazards(lines):
     pinned, bad = 0, []
     for i, l in enumerate(lines):
         op, ops = _split(l)
-        if not op.startswith("v_mfma") or not ops or not ops[0].startswith("v"):
+        if not op.startswith("v_mfma") or not ops:
+            continue
+        if not (ops[0].startswith("v") or (agpr_too and ops[0].startswith("a"))):
             continue
         pinned += 1
         dst = _regs(ops[0])
@@ -75,7 +81,7 @@ def find_hazards(lines):
                     continue
                 touched = set()
                 for x in oo:
-                    for tok in re.findall(r"v\[\d+:\d+\]|v\d+", x):
+                    for tok in re.findall(r"[va]\[\d+:\d+\]|\b[va]\d+\b", x):
                         touched |= _regs(tok)
                 if touched & dst:
                     bad.append(f"line {j}: touches the result of line {i + 1} after {t} states: {s}")
@@ -94,23 +100,81 @@ def find_hazards(lines):
     return pinned, bad
 
 
+WRITE_TO_MFMA = 4  # wait states between an instruction that writes a register and an asm MFMA that reads it
+
+
+def find_late_writers(lines):
+    """The other direction, for the MFMAs issued through inline asm (between the compiler's ASMSTART / ASMEND
+    marks): an instruction other than an MFMA that writes one of their operand registers must lie at least
+    WRITE_TO_MFMA wait states before them (the compiler inserts those states for the MFMAs it knows).  Scans
+    back inside the basic block; loads are waited for explicitly and are not instructions of this kind."""
+    bad, checked, in_asm = [], 0, False
+    for i, l in enumerate(lines):
+        s = l.strip()
+        if s.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if s.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        op, ops = _split(s)
+        if not in_asm or not op.startswith("v_mfma"):
+            continue
+        checked += 1
+        reads = set().union(*[_regs(x) for x in ops[1:]])
+        t, j = 0, i - 1
+        while j >= 0 and t < WRITE_TO_MFMA:
+            p = lines[j].strip()
+            j -= 1
+            if not p or p.startswith(";") or p.startswith("."):
+                if re.match(r"\.LBB\d+_\d+:", p):
+                    break
+                continue
+            o, oo = _split(p)
+            if o == "s_nop":
+                t += int(oo[0]) + 1
+                continue
+            if o.startswith("v_") and not o.startswith("v_mfma") and oo and (_regs(oo[0]) & reads):
+                bad.append(f"line {j + 2}: writes an operand of the asm MFMA at line {i + 1} only {t} states before it: {p}")
+                break
+            t += 1
+    return checked, bad
+
+
+def test_lint_flags_a_late_writer():
+    mf = ["\t;;#ASMSTART", "\tv_mfma_f32_16x16x32_bf16 a[0:3], v[90:93], v[54:57], a[0:3]", "\t;;#ASMEND"]
+    assert len(find_late_writers(["v_accvgpr_write_b32 a1, 0"] + mf)[1]) == 1
+    assert len(find_late_writers(["v_mov_b32_e32 v91, 0", "s_nop 1"] + mf)[1]) == 1
+    assert find_late_writers(["v_accvgpr_write_b32 a1, 0", "s_nop 3"] + mf) == (1, [])
+    assert find_late_writers(["v_accvgpr_write_b32 a9, 0"] + mf) == (1, [])
+    assert find_late_writers(["v_accvgpr_write_b32 a1, 0", mf[1]]) == (0, [])   # not an asm MFMA: the compiler's job
+
+
 def test_lint_flags_an_early_reader():
-    ok = ["v_mfma_f32_32x32x16_bf16 v[2:17], v[90:93], v[50:53], v[2:17]",
-          "v_mfma_f32_32x32x16_bf16 a[0:15], v[90:93], v[54:57], a[0:15]",
-          "v_mfma_f32_32x32x16_bf16 a[16:31], v[90:93], v[58:61], a[16:31]",
+    ok = ["v_mfma_f32_16x16x32_bf16 v[2:5], v[90:93], v[50:53], v[2:5]",
+          "v_mfma_f32_16x16x32_bf16 a[0:3], v[90:93], v[54:57], a[0:3]",
+          "v_mfma_f32_16x16x32_bf16 a[4:7], v[90:93], v[58:61], a[4:7]",
+          "v_mfma_f32_16x16x32_bf16 a[8:11], v[90:93], v[62:65], a[8:11]",
           "v_mov_b32_e32 v100, v2", "s_endpgm"]
     assert find_hazards(ok) == (1, [])
-    early = [ok[0], "s_nop 0", "v_mov_b32_e32 v100, v2", "s_endpgm"]
+    assert find_hazards(ok, agpr_too=True)[0] == 4
+    early = [ok[0], ok[1], "v_mov_b32_e32 v100, v2", "s_endpgm"]
     assert len(find_hazards(early)[1]) == 1
-    via_branch = [ok[0], "s_cbranch_scc1 .LBB0_1", ok[1], ok[2], "s_endpgm", ".LBB0_1:", "v_add_f32_e32 v3, v3, v4",
-                  "s_endpgm"]
+    via_branch = [ok[0], "s_cbranch_scc1 .LBB0_1", ok[1], ok[2], ok[3], "s_endpgm", ".LBB0_1:",
+                  "v_add_f32_e32 v3, v3, v4", "s_endpgm"]
     assert len(find_hazards(via_branch)[1]) == 1
     in_place = [ok[0], ok[0], "s_endpgm"]          # accumulating into the same registers again is fine
     assert find_hazards(in_place) == (2, [])
+    # an accumulator in the other register file read too early
+    early_agpr = [ok[1], "v_accvgpr_read_b32 v7, a1", "s_endpgm"]
+    assert find_hazards(early_agpr) == (0, [])
+    assert len(find_hazards(early_agpr, agpr_too=True)[1]) == 1
+    late_agpr = [ok[1], ok[2], ok[3], "v_accvgpr_read_b32 v7, a1", "s_endpgm"]
+    assert find_hazards(late_agpr, agpr_too=True) == (3, [])
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="no hipcc")
-def test_no_reader_follows_a_vgpr_accumulating_mfma_too_closely(tmp_path):
+def test_no_hazard_around_the_mfmas_of_the_compiled_kernels(tmp_path):
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     units = [u for u in moe_build.SOURCES if u.startswith("moe_gemm_")]   # every unit that instantiates the kernel
     assert len(units) == 7
@@ -126,9 +190,12 @@ def test_no_reader_follows_a_vgpr_accumulating_mfma_too_closely(tmp_path):
         outs = list(ex.map(compile_one, units))
     for out in outs:
         with open(out) as fh:
-            pinned, bad = find_hazards(fh.read().splitlines())
+            pinned, bad = find_hazards(fh.read().splitlines(), agpr_too=True)
         if out.endswith("pairsum.s"):
-            assert pinned == 0, f"{out}: the router-logit unit is built without the 288-row tile"
+            assert pinned > 0
         else:
-            assert pinned > 0, f"{out}: expected MFMAs with a VGPR destination (the ninth row block of the 288-row tile)"
+            assert pinned > 0, f"{out}: expected MFMAs"
         assert not bad, f"{out}:\n" + "\n".join(bad[:10])
+        with open(out) as fh:
+            n_asm, late = find_late_writers(fh.read().splitlines())
+        assert not late, f"{out}:\n" + "\n".join(late[:10])
