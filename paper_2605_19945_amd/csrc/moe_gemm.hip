@@ -43,11 +43,18 @@ int gemm_class_rows(int cls) { return kClassRows[cls]; }
 bool gemm_pick_stream(int cls, double rows_per_expert) { return rows_per_expert <= (double)kClassRows[cls]; }
 
 int gemm_pick_class(double rows_per_expert) {
-    // Measured (Mixtral shape and the expert-parallel share, layer time): below 12 rows per expert the
-    // 128-row class is the fastest of the weight-streaming launches (4 to 8 rows per expert: 0.225 / 0.238 /
-    // 0.235 ms for the classes 0 / 5 / 1 on the expert-parallel share); from 12 to 24 rows per expert the
-    // decode class (16 and 24 rows per expert on the Mixtral shape: 0.562 against 0.572 and 0.566 against
-    // 0.580 ms); above that the tall class (it wins from about 32 rows per expert upwards).
+    // Measured on the layer time of the Mixtral shape, near-uniform loads (ms; classes 5 / 0 / 1 = decode,
+    // 128-row, 288-row):
+    //     8 rows per expert   0.481 / 0.484 / 0.495        64 rows   0.656 / 0.527 / 0.539
+    //    32                   0.501 / 0.501 / 0.516        96        0.820 / 0.554 / 0.571
+    //    48                   0.515 / 0.515 / 0.528       128        0.980 / 0.657 / 0.587
+    // and of the expert-parallel share at 4 to 8 rows per expert: 0.225 / 0.238 / 0.235 for 0 / 5 / 1.
+    // A class loses as soon as experts need a second row tile of it (their weights are then streamed twice).
+    // On uniform loads the small classes would win by 2 to 3 % up to about three quarters of their tile
+    // height; but the host only knows the MEAN load, and under the skew this library is built for they lose
+    // more than that (expert-parallel share with Zipf loads, mean 64 rows per expert: 0.559 ms with the
+    // 128-row class against 0.517 with the tall one).  So the small classes are used only where even a hot
+    // expert stays inside one tile: below 12 rows per expert the 128-row class, up to 24 the decode class.
     if (rows_per_expert < 12.0) return GEMM_LOW;
     return rows_per_expert <= 24.0 ? GEMM_DECODE : GEMM_MAIN;
 }
