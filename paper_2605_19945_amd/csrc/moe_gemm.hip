@@ -142,9 +142,11 @@ int gemm_pick_split2(const GemmPlan& p, int64_t n_rows, int E_local, int d, int 
     const double w_bytes = (double)e_loaded * d * f * 2;
     const int KT = f / 64;
     if (p.cls == GEMM_DECODE) {
-        // decode class: the launch only streams weights; split until every compute unit holds as many workgroups
-        // as fit on it (each keeps two K steps of its weight panel in flight)
-        const double want = (double)SCHED_CU * kClassPerCu[GEMM_DECODE];
+        // decode class: the launch only streams weights.  Two wavefronts that read one sequential stream each
+        // keep a compute unit's share of the memory system busy, so the reduction is only split until every
+        // compute unit has a work item (Mixtral shape, 16 rows per expert, 256 items unsplit: 146 us; 2 splits
+        // 149; 4 splits, one item per resident workgroup, 156; 8 splits 164)
+        const double want = (double)SCHED_CU;
         int pick = 1;
         for (int s = 1; s <= 8; ++s) {
             if (KT % s != 0 || KT / s < 16) continue;
