@@ -141,6 +141,79 @@ def find_late_writers(lines):
     return checked, bad
 
 
+def find_touched_before_arrival(lines, limit=4000):
+    """The weight loads are inline asm too (global_load_dwordx4 between ASMSTART / ASMEND), waited for with
+    explicit counts: the compiler does not know that their destination registers are not valid yet and could
+    copy or reuse them.  From every such load, walk forward along the fall-through path (a taken branch is
+    followed, a conditional one is not) until an s_waitcnt whose vmcnt is no larger than the number of
+    vector-memory instructions issued since -- or the next barrier, in front of which the kernel waits with a
+    count it picks at run time -- and flag anything that names a destination register before that.  Returns
+    (loads checked, hazards)."""
+    labels = {}
+    for i, l in enumerate(lines):
+        m = re.match(r"(\.LBB\d+_\d+):", l)
+        if m:
+            labels[m.group(1)] = i
+    bad, checked, in_asm = [], 0, False
+    for i, l in enumerate(lines):
+        s = l.strip()
+        if s.startswith(";;#ASMSTART"):
+            in_asm = True
+            continue
+        if s.startswith(";;#ASMEND"):
+            in_asm = False
+            continue
+        op, ops = _split(s)
+        if not in_asm or not op.startswith("global_load_dwordx4"):
+            continue
+        checked += 1
+        dst = _regs(ops[0])
+        later, j, steps, seen = 0, i + 1, 0, set()
+        while j < len(lines) and steps < limit:
+            p = lines[j].strip()
+            j += 1
+            if not p or p.startswith(";") or p.startswith("."):
+                continue
+            steps += 1
+            o, oo = _split(p)
+            if o == "s_waitcnt":
+                m = re.search(r"vmcnt\((\d+)\)", p)
+                if m and int(m.group(1)) <= later:
+                    break
+                continue
+            if o == "s_barrier":
+                break  # every load is waited for (with a count chosen at run time) before the next barrier
+            touched = set()
+            for x in oo:
+                for tok in re.findall(r"[va]\[\d+:\d+\]|\b[va]\d+\b", x):
+                    touched |= _regs(tok)
+            if touched & dst:
+                bad.append(f"line {j}: names a register of the load at line {i + 1} before it has been waited for: {p}")
+                break
+            if o.startswith(("global_", "buffer_", "scratch_", "flat_")):
+                later += 1
+            if o == "s_endpgm":
+                break
+            if o == "s_branch":
+                if oo[0] in seen:
+                    break
+                seen.add(oo[0])
+                j = labels[oo[0]]
+    return checked, bad
+
+
+def test_lint_flags_a_register_used_before_its_load_arrived():
+    ld = ["\t;;#ASMSTART", "\tglobal_load_dwordx4 v[10:13], v1, s[2:3] offset:0", "\t;;#ASMEND"]
+    other = ["\t;;#ASMSTART", "\tglobal_load_dwordx4 v[20:23], v1, s[2:3] offset:1024", "\t;;#ASMEND"]
+    ok = ld + other + ["s_waitcnt vmcnt(1)", "v_mov_b32_e32 v5, v10", "s_endpgm"]
+    assert find_touched_before_arrival(ok)[1] == []
+    early = ld + other + ["v_mov_b32_e32 v5, v10", "s_waitcnt vmcnt(1)", "s_endpgm"]
+    assert len(find_touched_before_arrival(early)[1]) == 1
+    third = ["\t;;#ASMSTART", "\tglobal_load_dwordx4 v[30:33], v1, s[2:3] offset:2048", "\t;;#ASMEND"]
+    not_enough = ld + other + third + ["s_waitcnt vmcnt(3)", "v_mov_b32_e32 v5, v11", "s_waitcnt vmcnt(0)", "s_endpgm"]
+    assert len(find_touched_before_arrival(not_enough)[1]) == 1
+
+
 def test_lint_flags_a_late_writer():
     mf = ["\t;;#ASMSTART", "\tv_mfma_f32_16x16x32_bf16 a[0:3], v[90:93], v[54:57], a[0:3]", "\t;;#ASMEND"]
     assert len(find_late_writers(["v_accvgpr_write_b32 a1, 0"] + mf)[1]) == 1
@@ -199,3 +272,6 @@ def test_no_hazard_around_the_mfmas_of_the_compiled_kernels(tmp_path):
         with open(out) as fh:
             n_asm, late = find_late_writers(fh.read().splitlines())
         assert not late, f"{out}:\n" + "\n".join(late[:10])
+        with open(out) as fh:
+            n_loads, early = find_touched_before_arrival(fh.read().splitlines())
+        assert n_loads > 0 and not early, f"{out}:\n" + "\n".join(early[:10])
